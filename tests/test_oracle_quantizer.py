@@ -1,0 +1,165 @@
+"""Pins for the oracle's quantizer and storage formats (CPU only).
+
+Everything here checks `oracle/` against something other than itself: hand-worked
+cases of the paper's quantizer equation, explicit bytes, error bounds that follow
+from the definition, and a pure-Python re-derivation with exact rational arithmetic.
+"""
+import os
+import struct
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import dirotq_oracle as O
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "quantizer_cases.txt")
+
+
+def _cases():
+    out = []
+    with open(GOLDEN) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            vals, scale_hex, codes = [p.strip() for p in line.split("|")]
+            out.append((np.array([float(v) for v in vals.split()], np.float32),
+                        int(scale_hex, 16),
+                        np.array([int(c) for c in codes.split()], np.int8)))
+    return out
+
+
+def test_qmax_is_the_papers():
+    # quantizer equation: q_max = 2^(k-1) - 1 for k-bit symmetric integers
+    assert O.QMAX == 2 ** (4 - 1) - 1 == 7
+
+
+@pytest.mark.parametrize("vals,scale_bits,codes", _cases())
+def test_hand_worked_cases(vals, scale_bits, codes):
+    q, s = O.quantize_groups(vals[None, :], g=len(vals))
+    assert s.dtype == np.float16 and q.dtype == np.int8
+    assert int(s.view(np.uint16)[0, 0]) == scale_bits
+    np.testing.assert_array_equal(q[0], codes)
+
+
+def test_hand_cases_as_two_groups_of_one_row():
+    # groups are consecutive channels along the last axis: two 4-element cases
+    # side by side in one row give the two cases' answers side by side.
+    cs = _cases()
+    a, b = cs[0], cs[2]
+    row = np.concatenate([a[0], b[0]])[None, :]
+    q, s = O.quantize_groups(row, g=4)
+    np.testing.assert_array_equal(q[0], np.concatenate([a[2], b[2]]))
+    assert [int(v) for v in s.view(np.uint16)[0]] == [a[1], b[1]]
+
+
+def _f32(x):
+    return struct.unpack("f", struct.pack("f", x))[0]
+
+
+def _f16(x):
+    return struct.unpack("e", struct.pack("e", x))[0]
+
+
+def _quant_group_python(vals):
+    """The same op sequence with Python floats: fp32 results obtained by rounding an
+    fp64 result once (innocuous for +,*,/ of fp32 operands since 53 >= 2*24+2)."""
+    amax = max(abs(v) for v in vals)
+    s32 = min(_f32(amax / 7.0), 65504.0)
+    sf = _f16(s32)
+    if sf == 0.0:
+        return [0] * len(vals), 0.0
+    inv = _f32(1.0 / sf)
+    codes = []
+    for v in vals:
+        t = _f32(v * inv)
+        n = round(t)              # Python's round(): ties to even
+        codes.append(max(-7, min(7, n)))
+    return codes, sf
+
+
+def test_against_pure_python_sequence():
+    rng = np.random.default_rng(11)
+    v = (rng.standard_normal((64, 128)) * rng.lognormal(0, 2, size=(64, 1))).astype(np.float32)
+    v[3, 5:9] = 0.0
+    v[7, :32] = 0.0                              # one all-zero group
+    q, s = O.quantize_groups(v, g=32)
+    for m in range(64):
+        for j in range(4):
+            codes, sf = _quant_group_python([float(x) for x in v[m, 32 * j:32 * j + 32]])
+            assert float(s[m, j]) == sf
+            assert list(q[m, 32 * j:32 * j + 32]) == codes
+
+
+@pytest.mark.parametrize("g", [32, 64, 128])
+def test_invariants(g):
+    rng = np.random.default_rng(5)
+    v = (rng.standard_normal((200, 4 * g)) * rng.lognormal(0, 1.5, size=(200, 1))).astype(np.float32)
+    q, s = O.quantize_groups(v, g)
+    sf = s.astype(np.float64)
+    assert q.min() >= -7 and q.max() <= 7
+    vg = v.reshape(200, 4, g).astype(np.float64)
+    qg = q.reshape(200, 4, g)
+    amax = np.abs(vg).max(-1)
+    # the largest-magnitude element gets code +-7 with the sign of the element
+    pos = np.abs(vg).argmax(-1)
+    top = np.take_along_axis(qg, pos[..., None], -1)[..., 0]
+    vtop = np.take_along_axis(vg, pos[..., None], -1)[..., 0]
+    np.testing.assert_array_equal(top, 7 * np.sign(vtop).astype(np.int8))
+    # stored scale is amax/7 to within fp16 rounding (2^-11 relative)
+    assert np.all(np.abs(sf * 7 - amax) <= amax * 2.0 ** -11 * (1 + 1e-6))
+    # dequantisation error at most half a step (+ the clip at the top code, where the
+    # fp16 rounding of the scale can leave amax up to 7 * 2^-11 steps above 7 s)
+    err = np.abs(vg - qg * sf[..., None])
+    assert np.all(err <= sf[..., None] * (0.5 + 7 * 2.0 ** -11 + 1e-6))
+    # dequantize_groups is codes * scale
+    np.testing.assert_array_equal(O.dequantize_groups(q, s, g).reshape(200, 4, g), qg * sf[..., None])
+
+
+def test_exact_rational_rounding_agrees_away_from_ties():
+    """The real-arithmetic definition round(v / s) agrees with the fp32 sequence
+    except within ~1 ulp of a rounding boundary."""
+    rng = np.random.default_rng(9)
+    v = rng.standard_normal((40, 64)).astype(np.float32)
+    q, s = O.quantize_groups(v, 64)
+    for m in range(40):
+        sf = Fraction(float(s[m, 0]))
+        for k in range(64):
+            t = Fraction(float(v[m, k])) / sf
+            frac = t - (t.numerator // t.denominator)
+            if abs(frac - Fraction(1, 2)) < Fraction(1, 10 ** 5):
+                continue
+            assert int(q[m, k]) == max(-7, min(7, round(t)))
+
+
+def test_pack_bytes_and_roundtrip():
+    # byte i = channel 2i in bits 0-3, channel 2i+1 in bits 4-7, two's complement
+    assert O.pack_int4(np.array([-7, 7], np.int8))[0] == 0x79
+    assert O.pack_int4(np.array([7, -7], np.int8))[0] == 0x97
+    assert O.pack_int4(np.array([1, 0], np.int8))[0] == 0x01
+    assert O.pack_int4(np.array([0, 1], np.int8))[0] == 0x10
+    assert O.pack_int4(np.array([-1, -1], np.int8))[0] == 0xFF
+    pairs = np.array([[a, b] for a in range(-7, 8) for b in range(-7, 8)], np.int8)
+    packed = O.pack_int4(pairs)
+    assert packed.shape == (225, 1) and packed.dtype == np.uint8
+    np.testing.assert_array_equal(O.unpack_int4(packed), pairs)
+    row = np.arange(-7, 7, dtype=np.int8)[None, :]                 # 14 channels -> 7 bytes
+    np.testing.assert_array_equal(O.unpack_int4(O.pack_int4(row)), row)
+
+
+def test_bf16_rounding():
+    # 1 + 2^-8 is a tie between 1.0 and 1 + 2^-7: even mantissa wins (1.0);
+    # 1 + 3*2^-8 is a tie between 1+2^-7 and 1+2^-6: goes to 1 + 2^-6.
+    a = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20,
+                  -3.0, 0.0, 2.0 ** -130], np.float32)
+    r = O.round_to_bf16(a)
+    np.testing.assert_array_equal(
+        r, np.array([1.0, 1.0 + 2.0 ** -6, 1.0 + 2.0 ** -7, -3.0, 0.0, 2.0 ** -130], np.float32))
+    np.testing.assert_array_equal(O.bf16_bits(r)[:2], np.array([0x3F80, 0x3F82], np.uint16))
+    np.testing.assert_array_equal(O.from_bf16_bits(O.bf16_bits(r)), r)
+    # agrees with torch's cast on random data
+    import torch
+    x = np.random.default_rng(0).standard_normal(10000).astype(np.float32) * 37.0
+    t = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    np.testing.assert_array_equal(O.round_to_bf16(x), t)
