@@ -1,0 +1,152 @@
+/*
+ * dirotq.h -- C ABI of the MI355X (gfx950) implementation of the rotation-aware
+ * W4A4 linear layer of DiRotQ ("PCA-guided rotated quantization", Section 4.2 of
+ * the paper; forward-computation equation at the end of that section).
+ *
+ * The layer replaces  y = W x  (W in R^{N x K}) by
+ *
+ *     x_hat = x Q                                   online rotation into the PCA basis
+ *     x_h   = bf16(x_hat[:, 0:r])                   top-r coefficients, kept in 16 bit
+ *     x_l   = int4(x_hat[:, r:K]) with fp16 scales  per token, per group of g channels
+ *     y     = x_h W'_h^T + sum_j s_x[:,j] s_w[:,j]^T * (q_x,j q_w,j^T)
+ *
+ * where W' = W Q is fused, split at r and quantized offline.  Names: M tokens,
+ * K input channels, N output channels, r = rank of the 16-bit subspace (the
+ * paper's k), g = group size, G = (K - r) / g.  The paper writes Y = X W with
+ * W in R^{m x n}; this header uses the nn.Linear convention, W' = (V^T W_paper)^T.
+ *
+ * The quantizer is the symmetric form of the paper's quantizer equation
+ * (Section 3): s = max|v| / 7 over a group, stored as IEEE fp16; code =
+ * clip(round-half-even(v / s), -7, 7).  In detail, in IEEE fp32:
+ * amax = max|v|; s = fp16_rne(min(amax / 7, 65504)); s == 0 -> all codes 0; else
+ * inv = 1 / float(s), code = clip(rint(v * inv), -7, 7).
+ *
+ * General conventions
+ *  - Every pointer is a DEVICE pointer unless marked "host".  The caller owns all
+ *    memory; the library never allocates or frees device memory.
+ *  - All matrices are dense row-major.  Device pointers must be 16-byte aligned.
+ *  - 16-bit floats are passed as uint16_t bit patterns (bfloat16 or IEEE half).
+ *  - Calls enqueue work on `stream` (a hipStream_t passed as void*; NULL = the
+ *    default stream) and return without synchronizing.
+ *  - Return value: DIROTQ_OK or a negative dirotq_status.  Argument errors are
+ *    detected on the host before anything is enqueued; nothing is written then.
+ *  - Supported shapes: M >= 0 (M == 0 is a no-op), N >= 1, K a multiple of 32,
+ *    0 <= r <= K with r a multiple of 32, g in {32, 64, 128}, (K - r) % g == 0.
+ *  - INT4 packing (activations): byte i of a row holds channel 2i of the 4-bit part
+ *    in bits 0-3 and channel 2i+1 in bits 4-7, two's-complement nibbles.
+ *  - Activation scales are group-major: s_x[j * M + m] for group j, token m.
+ */
+#ifndef DIROTQ_H
+#define DIROTQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  DIROTQ_OK = 0,
+  DIROTQ_ERR_NULL = -1,        /* a required pointer is NULL */
+  DIROTQ_ERR_SHAPE = -2,       /* M<0, N<1, K<32, K%32, r<0, r>K, r%32, g not in {32,64,128}, (K-r)%g */
+  DIROTQ_ERR_ALIGN = -3,       /* a device pointer is not 16-byte aligned */
+  DIROTQ_ERR_WORKSPACE = -4,   /* workspace / scratch / blob buffer too small */
+  DIROTQ_ERR_UNSUPPORTED = -5, /* valid request this build does not implement */
+  DIROTQ_ERR_HIP = -6          /* a HIP call failed; see dirotq_last_hip_error() */
+} dirotq_status;
+
+/* Static description of a status code (never freed; host). */
+const char* dirotq_strerror(int status);
+
+/* hipError_t (as int) of the last DIROTQ_ERR_HIP on this host thread, else 0. */
+int dirotq_last_hip_error(void);
+
+/* ---- size queries (host, pure) ------------------------------------------------ */
+
+/* Bytes of the prepared-weight blob for an N x K layer split at r with groups of g. */
+int dirotq_weights_bytes(int N, int K, int r, int g, size_t* bytes /*host out*/);
+
+/* Bytes of scratch dirotq_prepare_weights needs (the fp32 fused weight W Q). */
+int dirotq_prepare_scratch_bytes(int N, int K, size_t* bytes /*host out*/);
+
+/* Bytes of workspace dirotq_linear needs (x_h, packed x_l and s_x of one call). */
+int dirotq_workspace_bytes(int M, int K, int r, int g, size_t* bytes /*host out*/);
+
+/* ---- offline ------------------------------------------------------------------- */
+
+/*
+ * Rotation operand for the online kernel: Qt[c * K + k] = bf16_rne(Q[k * K + c]).
+ * Q is the orthogonal basis V = [U_h, U_l R] of Section 4.2, fp32 [K,K], column c =
+ * c-th basis direction (eigenvalues descending).  Qt is bf16 [K,K], one basis
+ * direction per row, which is the layout the rotation GEMM streams.
+ */
+int dirotq_prepare_rotation(const float* Q, int K, uint16_t* Qt_bf16 /*out*/, void* stream);
+
+/*
+ * Offline weight fusion ("absorbed into the weights offline", Section 4.2):
+ * W' = W Q with fp64 accumulation rounded to fp32; W'_h = bf16_rne(W'[:, 0:r]);
+ * W'[:, r:K] quantized per output channel and per group of g with the quantizer
+ * above (round-to-nearest stands in for GPTQ).  W fp32 [N,K], Q fp32 [K,K] as in
+ * dirotq_prepare_rotation.  `blob` receives dirotq_weights_bytes bytes in a layout
+ * private to this library (read it back with dirotq_export_weights).  `scratch`:
+ * dirotq_prepare_scratch_bytes bytes, contents undefined afterwards.
+ */
+int dirotq_prepare_weights(const float* W, const float* Q, int N, int K, int r, int g,
+                           void* blob /*out*/, void* scratch, size_t scratch_bytes, void* stream);
+
+/*
+ * Build a blob from already-quantized weights: Wh bf16 [N,r], codes int8 [N,K-r]
+ * with values in [-7,7], sw fp16 [N,G] (channel-major).  Wh may be NULL when r == 0,
+ * codes and sw may be NULL when r == K.
+ */
+int dirotq_import_weights(const uint16_t* Wh_bf16, const int8_t* codes, const uint16_t* sw_fp16,
+                          int N, int K, int r, int g, void* blob /*out*/, void* stream);
+
+/* Inverse of dirotq_import_weights (outputs may be NULL to skip them). */
+int dirotq_export_weights(const void* blob, int N, int K, int r, int g,
+                          uint16_t* Wh_bf16 /*out [N,r]*/, int8_t* codes /*out [N,K-r]*/,
+                          uint16_t* sw_fp16 /*out [N,G]*/, void* stream);
+
+/* ---- online -------------------------------------------------------------------- */
+
+/*
+ * Rotation, split and activation quantization (rotation/split equation of Section
+ * 4.2 and the quantizer of Section 3) in one kernel: x_hat = x Q accumulated in fp32
+ * from bf16 operands; channels [0,r) are rounded to bf16, channels [r,K) are
+ * quantized per token and per group from the fp32 accumulator.
+ *   x_bf16   [M,K]          activations
+ *   Qt_bf16  [K,K]          from dirotq_prepare_rotation
+ *   xh_bf16  [M,r]    out   (may be NULL when r == 0)
+ *   xl_packed[M,(K-r)/2] out  packed INT4 codes (may be NULL when r == K)
+ *   sx_fp16  [G,M]    out   group-major scales (may be NULL when r == K)
+ */
+int dirotq_rotate_quantize(const uint16_t* x_bf16, const uint16_t* Qt_bf16, int M, int K, int r, int g,
+                           uint16_t* xh_bf16, uint8_t* xl_packed, uint16_t* sx_fp16, void* stream);
+
+/*
+ * Mixed-precision product (forward-computation equation of Section 4.2):
+ *   y[m,n] = sum_{k<r} xh[m,k] W'_h[n,k]
+ *          + sum_j float(sx[j,m]) float(sw[n,j]) * I[m,n,j]  (+ bias[n])
+ * with I[m,n,j] the exact integer dot product of the INT4 codes of group j,
+ * everything accumulated in fp32.  Inputs as produced by dirotq_rotate_quantize and
+ * dirotq_prepare_weights / dirotq_import_weights.  bias_bf16 [N] may be NULL.
+ * y_dtype 0: y is bf16 [M,N] (round to nearest even); 1: y is fp32 [M,N].
+ */
+int dirotq_w4a4_gemm(const uint16_t* xh_bf16, const uint8_t* xl_packed, const uint16_t* sx_fp16,
+                     const void* blob, const uint16_t* bias_bf16, int M, int N, int K, int r, int g,
+                     void* y /*out*/, int y_dtype, void* stream);
+
+/*
+ * The fused layer: dirotq_rotate_quantize into `workspace`, then dirotq_w4a4_gemm,
+ * both on `stream`.  y_bf16 [M,N].  workspace: dirotq_workspace_bytes bytes, 256-byte
+ * aligned; its contents afterwards are the intermediates of this call.
+ */
+int dirotq_linear(const uint16_t* x_bf16, const uint16_t* Qt_bf16, const void* blob,
+                  const uint16_t* bias_bf16, int M, int N, int K, int r, int g,
+                  uint16_t* y_bf16 /*out*/, void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DIROTQ_H */

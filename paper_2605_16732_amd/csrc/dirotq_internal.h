@@ -1,0 +1,108 @@
+// Internal declarations shared by the translation units of libdirotq (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "dirotq.h"
+
+namespace dirotq {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) int i32x16;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a; }
+
+// Layout of the prepared-weight blob.  Three sections, each 256-byte aligned:
+//   wh    bf16 [N][r]            16-bit branch of W' = W Q
+//   codes u8   [N][(K-r)/2]      INT4 codes of W'[:, r:], two per byte (even channel low)
+//   sw    fp16 [G][N]            group-major scales
+struct BlobLayout {
+  size_t off_wh, off_codes, off_sw, bytes;
+};
+inline BlobLayout blob_layout(int N, int K, int r, int g) {
+  BlobLayout L;
+  const size_t G = (size_t)(K - r) / g;
+  L.off_wh = 0;
+  L.off_codes = align_up((size_t)N * r * 2);
+  L.off_sw = L.off_codes + align_up((size_t)N * (K - r) / 2);
+  L.bytes = L.off_sw + align_up(G * N * 2);
+  if (L.bytes == 0) L.bytes = kAlign;
+  return L;
+}
+
+// Workspace of dirotq_linear: xh bf16 [M][r] | xl u8 [M][(K-r)/2] | sx fp16 [G][M].
+struct WorkspaceLayout {
+  size_t off_xh, off_xl, off_sx, bytes;
+};
+inline WorkspaceLayout workspace_layout(int M, int K, int r, int g) {
+  WorkspaceLayout L;
+  const size_t G = (size_t)(K - r) / g;
+  L.off_xh = 0;
+  L.off_xl = align_up((size_t)M * r * 2);
+  L.off_sx = L.off_xl + align_up((size_t)M * (K - r) / 2);
+  L.bytes = L.off_sx + align_up(G * M * 2);
+  if (L.bytes == 0) L.bytes = kAlign;
+  return L;
+}
+
+int check_shape(long M, long N, long K, long r, long g);   // DIROTQ_OK or DIROTQ_ERR_SHAPE
+inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+int hip_failed(hipError_t e);                               // records e, returns DIROTQ_ERR_HIP
+
+// kernel launchers (arguments already validated)
+int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g,
+                           uint16_t* xh, uint8_t* xl, uint16_t* sx, hipStream_t s);
+int launch_w4a4_gemm(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const void* blob,
+                     const uint16_t* bias, int M, int N, int K, int r, int g, void* y, int y_dtype,
+                     hipStream_t s);
+int launch_prepare_rotation(const float* Q, int K, uint16_t* Qt, hipStream_t s);
+int launch_prepare_weights(const float* W, const float* Q, int N, int K, int r, int g, void* blob,
+                           float* scratch, hipStream_t s);
+int launch_import_weights(const uint16_t* Wh, const int8_t* codes, const uint16_t* sw, int N, int K,
+                          int r, int g, void* blob, hipStream_t s);
+int launch_export_weights(const void* blob, int N, int K, int r, int g, uint16_t* Wh, int8_t* codes,
+                          uint16_t* sw, hipStream_t s);
+
+#if defined(__HIPCC__)
+// ---- device helpers ---------------------------------------------------------
+
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  // round to nearest even; inputs are finite in this library
+  uint32_t u = __builtin_bit_cast(uint32_t, f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) {
+  return __builtin_bit_cast(float, (uint32_t)b << 16);
+}
+__device__ __forceinline__ float f16_bits_to_f32(uint16_t b) {
+  return (float)__builtin_bit_cast(_Float16, b);
+}
+
+// Scale of one quantization group from its absolute maximum (symmetric form of the
+// paper's quantizer equation, q_max = 7): fp16_rne(min(amax / 7, 65504)).
+// Returns the stored scale as float and its bit pattern.
+__device__ __forceinline__ float group_scale(float amax, uint16_t& bits) {
+  float s32 = fminf(amax / 7.0f, 65504.0f);      // IEEE-rounded division
+  _Float16 h = (_Float16)s32;                     // round to nearest even
+  bits = __builtin_bit_cast(uint16_t, h);
+  return (float)h;
+}
+// Reciprocal used for the codes: 1 / s, IEEE-rounded; 0 for an all-zero group.
+__device__ __forceinline__ float group_inv(float sf) { return sf == 0.0f ? 0.0f : 1.0f / sf; }
+// 4-bit code of v: clip(rint(v * inv), -7, 7), ties to even.
+__device__ __forceinline__ int quant_code(float v, float inv) {
+  float t = rintf(v * inv);
+  t = fminf(fmaxf(t, -7.0f), 7.0f);
+  return (int)t;
+}
+#endif
+
+}  // namespace dirotq

@@ -180,7 +180,7 @@ def make_layer(shape: LayerShape, seed: int = 0, residual_rotation: bool = False
     if residual_rotation and shape.r < K:
         R = random_orthogonal(K - shape.r, seed)
         Q = np.concatenate([Q[:, :shape.r], Q[:, shape.r:] @ R], axis=1)
-    Q32 = Q.astype(np.float32)
+    Q32 = np.ascontiguousarray(Q, dtype=np.float32)
     del Q
     Z = _rng(seed, shape, 3).standard_normal((M, K), dtype=np.float32)
     x_bits = to_bf16_bits(Z * s[None, :])

@@ -1,0 +1,278 @@
+"""GPU parity: the HIP path (through the C-ABI) against the CPU oracle on the same
+seeded inputs.  Integer / byte / index results are compared bit for bit; floating
+point within tolerances stated at each test."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dirotq_oracle as O
+from paper_2605_16732_amd import binding as B
+from paper_2605_16732_amd import inputs as I
+
+from gpu_util import (check_codes_statistical, check_output, dev, dev_bf16, gpu_rotate_quantize, host_bf16_bits,
+                      host_f16, import_blob, layer_with_oracle)
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+# ------------------------------------------------------------------ offline side
+def test_prepare_rotation_is_bf16_transpose():
+    rng = np.random.default_rng(0)
+    K = 160
+    Q = rng.standard_normal((K, K)).astype(np.float32)
+    Qt = B.prepare_rotation(dev(Q))
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host_bf16_bits(Qt), O.bf16_bits(O.round_to_bf16(Q.T)))
+
+
+@pytest.mark.parametrize("N,K,r,g", [(70, 128, 32, 32), (129, 256, 0, 64), (64, 256, 128, 128), (33, 96, 96, 32)])
+def test_import_export_roundtrip(N, K, r, g):
+    _say(f"import/export N={N} K={K} r={r} g={g}")
+    rng = np.random.default_rng(1)
+    G = (K - r) // g
+    Wh = O.round_to_bf16(rng.standard_normal((N, r)).astype(np.float32))
+    qw = rng.integers(-7, 8, size=(N, K - r)).astype(np.int8)
+    sw = rng.lognormal(-3, 1, size=(N, G)).astype(np.float16)
+    blob = import_blob(Wh, qw, sw, N, K, r, g)
+    Wh2, qw2, sw2 = B.export_weights(blob, N, K, r, g)
+    torch.cuda.synchronize()
+    if r:
+        np.testing.assert_array_equal(host_bf16_bits(Wh2), O.bf16_bits(Wh))
+    if r < K:
+        np.testing.assert_array_equal(qw2.cpu().numpy(), qw)
+        np.testing.assert_array_equal(host_f16(sw2).view(np.uint16), sw.view(np.uint16))
+
+
+@pytest.mark.parametrize("N,K,r,g", [(100, 256, 32, 32), (192, 1152, 64, 64), (65, 384, 0, 128)])
+def test_prepare_weights_matches_oracle(N, K, r, g):
+    """W' = W Q in fp64 on both sides: stored scales, codes and the bf16 part agree bit
+    for bit except where an fp64 sum lands within rounding noise of an fp32 tie (allow
+    1e-5 of the elements, each off by one code / one bf16 ulp)."""
+    _say(f"prepare_weights N={N} K={K} r={r} g={g}")
+    rng = np.random.default_rng(2)
+    Q64, _ = np.linalg.qr(rng.standard_normal((K, K)))
+    Q32 = Q64.astype(np.float32)
+    W = (rng.standard_normal((N, K)) / np.sqrt(K)).astype(np.float32)
+    Wh, qw, sw = O.prepare_weights(W, Q32, r, g)
+    blob = B.prepare_weights(dev(W), dev(Q32), r, g)
+    Wh2, qw2, sw2 = B.export_weights(blob, N, K, r, g)
+    torch.cuda.synchronize()
+    if r:
+        a, b = host_bf16_bits(Wh2).astype(np.int32), O.bf16_bits(Wh).astype(np.int32)
+        assert np.abs(a - b).max() <= 1 and (a != b).mean() <= 1e-5
+    if r < K:
+        q2 = qw2.cpu().numpy()
+        assert (q2 != qw).mean() <= 1e-5 and np.abs(q2.astype(np.int32) - qw).max() <= 1
+        assert (host_f16(sw2).view(np.uint16) != sw.view(np.uint16)).mean() <= 1e-4
+
+
+# ------------------------------------------------------------------ kernel A, exact
+def _signed_perm(K, seed):
+    rng = np.random.default_rng(seed)
+    Q = np.zeros((K, K), np.float32)
+    Q[rng.permutation(K), np.arange(K)] = rng.choice([-1.0, 1.0], size=K)
+    return Q
+
+
+@pytest.mark.parametrize("M,K,r,g,perm", [
+    (300, 256, 64, 64, False), (300, 256, 32, 32, True), (129, 384, 0, 128, True),
+    (1, 128, 32, 32, False), (257, 1152, 64, 64, True), (64, 96, 96, 32, True), (130, 448, 64, 128, True),
+])
+def test_rotate_quantize_exact_with_permutation_basis(M, K, r, g, perm):
+    """With Q a (signed) permutation the rotation is exact in any summation order, so
+    bf16 part, codes and scales must equal the oracle's bit for bit."""
+    _say(f"rotate_quantize exact M={M} K={K} r={r} g={g} perm={perm}")
+    rng = np.random.default_rng(3)
+    Q = _signed_perm(K, 5) if perm else np.eye(K, dtype=np.float32)
+    x = O.round_to_bf16((rng.standard_normal((M, K)) * rng.lognormal(0, 1.5, size=(1, K))).astype(np.float32))
+    x[M // 2, :] = 0.0                                   # an all-zero token: scale 0, codes 0
+    x[0, :32] = O.round_to_bf16(np.float32(2.0 ** -26) * rng.integers(-9, 10, 32).astype(np.float32))
+    Qt = B.prepare_rotation(dev(Q))
+    xh_r, qx_r, sx_r = O.rotate_quantize(x, Q, r, g)
+    _, (xh_g, qx_g, sx_g) = gpu_rotate_quantize(O.bf16_bits(x), Qt, r, g)
+    np.testing.assert_array_equal(xh_g, xh_r)
+    np.testing.assert_array_equal(sx_g.view(np.uint16), sx_r.view(np.uint16))
+    np.testing.assert_array_equal(qx_g, qx_r)
+
+
+def test_rotate_quantize_ties_and_clip():
+    """Hand-built rows: ties at .5 (round half to even), a negative absmax, a scale
+    that is an fp16 subnormal so that the top code clips."""
+    K, r, g = 64, 0, 32
+    x = np.zeros((4, K), np.float32)
+    x[0, :4] = [7, -3.5, 0.5, 1.5]
+    x[0, 32:36] = [2.5, -2.5, 3.5, -7]
+    x[1, :4] = [14, 1, -3, 5]
+    x[1, 32:36] = [-3.5, 3.25, 0.25, -0.75]
+    x[2, :3] = np.array([9.75, -1.375, 1.0], np.float32) * np.float32(2.0 ** -24)   # amax/7 ~ 1.39 * 2^-24
+    x[3, :2] = [7 * 2.0 ** -25, 2.0 ** -26]                                          # scale ties down to 0
+    assert np.array_equal(O.round_to_bf16(x), x)
+    Qt = B.prepare_rotation(dev(np.eye(K, dtype=np.float32)))
+    _, qx_r, sx_r = O.rotate_quantize(x, np.eye(K, dtype=np.float32), r, g)
+    _, (_, qx_g, sx_g) = gpu_rotate_quantize(O.bf16_bits(x), Qt, r, g)
+    assert list(qx_r[0, :4]) == [7, -4, 0, 2] and list(qx_r[0, 32:36]) == [2, -2, 4, -7]
+    assert list(qx_r[2, :3]) == [7, -1, 1] and int(sx_r.view(np.uint16)[2, 0]) == 1
+    assert not qx_r[3].any() and int(sx_r.view(np.uint16)[3, 0]) == 0
+    np.testing.assert_array_equal(sx_g.view(np.uint16), sx_r.view(np.uint16))
+    np.testing.assert_array_equal(qx_g, qx_r)
+
+
+# ------------------------------------------------------------------ kernel B, exact
+@pytest.mark.parametrize("M,N,K,g", [(130, 200, 256, 32), (257, 136, 448, 64), (64, 129, 384, 128), (5, 8, 64, 32)])
+def test_w4a4_integer_dot_is_exact(M, N, K, g):
+    """Unit scales, no 16-bit branch: the fp32 output is the plain integer dot product
+    (< 2^24), so it must be exact -- the int32 group accumulators are bit-exact."""
+    _say(f"w4a4 integer M={M} N={N} K={K} g={g}")
+    rng = np.random.default_rng(4)
+    G = K // g
+    qx = rng.integers(-7, 8, size=(M, K)).astype(np.int8)
+    qw = rng.integers(-7, 8, size=(N, K)).astype(np.int8)
+    qx[0, :] = 7
+    qw[0, :] = -7                                         # extreme: I = -49 g per group
+    blob = import_blob(np.zeros((N, 0), np.float32), qw, np.ones((N, G), np.float16), N, K, 0, g)
+    xl = dev(O.pack_int4(qx))
+    sx = dev(np.ones((G, M), np.float16))
+    y = B.w4a4_gemm(None, xl, sx, blob, M, N, K, 0, g, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    want = (qx.astype(np.int64) @ qw.astype(np.int64).T).astype(np.float32)
+    np.testing.assert_array_equal(y.cpu().numpy(), want)
+    assert want[0, 0] == -49 * K
+
+
+def test_w4a4_power_of_two_scales_exact():
+    """Power-of-two scales keep every product and partial sum exact in fp32."""
+    rng = np.random.default_rng(6)
+    M, N, K, g = 96, 72, 256, 64
+    G = K // g
+    qx = rng.integers(-7, 8, size=(M, K)).astype(np.int8)
+    qw = rng.integers(-7, 8, size=(N, K)).astype(np.int8)
+    sx = (2.0 ** rng.integers(-3, 3, size=(M, G))).astype(np.float16)
+    sw = (2.0 ** rng.integers(-4, 2, size=(N, G))).astype(np.float16)
+    blob = import_blob(np.zeros((N, 0), np.float32), qw, sw, N, K, 0, g)
+    y = B.w4a4_gemm(None, dev(O.pack_int4(qx)), dev(np.ascontiguousarray(sx.T)), blob, M, N, K, 0, g,
+                    out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    want, _ = O.combine(np.zeros((M, 0), np.float32), qx, sx, np.zeros((N, 0), np.float32), qw, sw, g)
+    np.testing.assert_array_equal(y.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("M,N,K,r,g,use_bias", [
+    (200, 136, 320, 64, 64, True), (130, 129, 288, 32, 32, False), (64, 64, 256, 128, 128, True),
+    (77, 40, 128, 128, 32, False), (300, 264, 1152, 64, 64, False),
+])
+def test_w4a4_gemm_matches_oracle_on_identical_inputs(M, N, K, r, g, use_bias):
+    """Same x_h, codes, scales and weights on both sides.  fp32 accumulation of at most
+    G + r/16 partial terms against a float64 sum: 1e-5 of the largest output magnitude
+    per element is ample (observed ~1e-6); bf16 output equals the rounded fp32 output
+    except where the fp32 values straddle a bf16 tie (allow one bf16 ulp)."""
+    _say(f"w4a4 vs oracle M={M} N={N} K={K} r={r} g={g} bias={use_bias}")
+    rng = np.random.default_rng(7)
+    G = (K - r) // g
+    xh = O.round_to_bf16(rng.standard_normal((M, r)).astype(np.float32) * 20)
+    Wh = O.round_to_bf16(rng.standard_normal((N, r)).astype(np.float32) * 0.05)
+    qx = rng.integers(-7, 8, size=(M, K - r)).astype(np.int8)
+    qw = rng.integers(-7, 8, size=(N, K - r)).astype(np.int8)
+    sx = rng.lognormal(-1, 1, size=(M, G)).astype(np.float16)
+    sw = rng.lognormal(-5, 1, size=(N, G)).astype(np.float16)
+    bias = O.round_to_bf16(rng.standard_normal(N).astype(np.float32)) if use_bias else None
+    y32, ybf = O.combine(xh, qx, sx, Wh, qw, sw, g, bias)
+    blob = import_blob(Wh, qw, sw, N, K, r, g)
+    args = (dev_bf16(O.bf16_bits(xh)) if r else None, dev(O.pack_int4(qx)) if r < K else None,
+            dev(np.ascontiguousarray(sx.T)) if r < K else None, blob, M, N, K, r, g)
+    bias_d = dev_bf16(O.bf16_bits(bias)) if use_bias else None
+    yf = B.w4a4_gemm(*args, bias=bias_d, out_dtype=torch.float32).cpu().numpy()
+    yb = B.w4a4_gemm(*args, bias=bias_d, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    scale = np.abs(y32).max()
+    assert np.abs(yf - y32).max() <= 1e-5 * scale
+    a = host_bf16_bits(yb).astype(np.int32)
+    np.testing.assert_array_equal(a, O.bf16_bits(O.round_to_bf16(yf)).astype(np.int32))   # own rounding is RNE
+    assert np.abs(O.from_bf16_bits(host_bf16_bits(yb)) - ybf).max() <= 2.0 ** -7 * scale
+
+
+# ------------------------------------------------------------------ end to end
+def _end_to_end(shape, M=None, rows=None):
+    L, (Wh, qw, sw), ref = layer_with_oracle(shape, M=M, rows=rows)
+    Mx, K, N, r, g = L.x_bits.shape[0], shape.K, shape.N, shape.r, shape.g
+    Qt = B.prepare_rotation(dev(L.Q32))
+    np.testing.assert_array_equal(host_bf16_bits(Qt), np.ascontiguousarray(L.Q_bits.T))
+    blob = import_blob(Wh, qw, sw, N, K, r, g)
+    # stage 1: rotation + quantization against the oracle's
+    (xh_d, xl_d, sx_d), (xh_g, qx_g, sx_g) = gpu_rotate_quantize(L.x_bits, Qt, r, g)
+    sel = slice(None) if rows is None else np.asarray(rows)
+    stats = check_codes_statistical(ref["xhat"][:, r:], qx_g[sel], sx_g[sel], ref["qx"], ref["sx"], g)
+    if r:
+        ulp = np.abs(O.bf16_bits(xh_g[sel]).astype(np.int32) - O.bf16_bits(ref["xh"]).astype(np.int32))
+        assert ulp.max() <= 1 and (ulp != 0).mean() <= 2e-3      # fp32-sum noise across a bf16 tie
+    # stage 2: GEMM on the GPU's own intermediates against the oracle's combine of the same
+    y32_same, _ = O.combine(xh_g[sel], qx_g[sel], sx_g[sel], Wh, qw, sw, g)
+    yf = B.w4a4_gemm(xh_d if r else None, xl_d, sx_d, blob, Mx, N, K, r, g, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert np.abs(yf.cpu().numpy()[sel] - y32_same).max() <= 1e-5 * np.abs(y32_same).max()
+    # the fused entry point, bf16 out, against the oracle end to end
+    y = B.linear(dev_bf16(L.x_bits), Qt, blob, N, r, g)
+    torch.cuda.synchronize()
+    yg = O.from_bf16_bits(host_bf16_bits(y))
+    row_err, max_err = check_output(yg[sel], ref["y32"], tol=1e-2)
+    # and it is exactly the two-step path
+    y2 = B.w4a4_gemm(xh_d if r else None, xl_d, sx_d, blob, Mx, N, K, r, g, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)
+    _say(f"{shape.name}: codes agree {stats['agree']:.6f}, code flips {stats['code_flips']}, scale flips "
+         f"{stats['scale_flips']}/{stats['groups']}, out row-rel {row_err:.2e} max-rel {max_err:.2e}")
+    return stats
+
+
+def test_end_to_end_small_config():
+    _end_to_end(I.SMALL)
+
+
+def test_end_to_end_ragged_tokens_and_outputs():
+    # ragged M (several tiles + tail) and N not a multiple of the tile, r = 0 and g = 32
+    shp = I.LayerShape("ragged", 333, 384, 200, 0, 32, 4, 7, 0)
+    _end_to_end(shp)
+    shp = I.LayerShape("ragged128", 141, 640, 264, 128, 128, 4, 7, 1)
+    _end_to_end(shp)
+
+
+def test_end_to_end_pixart_fc1_sampled_rows():
+    # full PixArt fc1 launch; the oracle is evaluated on 96 sampled tokens
+    shp = I.PIXART[2]
+    rows = np.random.default_rng(0).choice(shp.M, size=96, replace=False)
+    rows.sort()
+    _end_to_end(shp, rows=rows)
+
+
+def test_rank_equals_K_is_a_bf16_gemm():
+    shp = I.LayerShape("allhigh", 150, 256, 96, 256, 32, 4, 7, 2)
+    L, (Wh, qw, sw), ref = layer_with_oracle(shp)
+    Qt = B.prepare_rotation(dev(L.Q32))
+    blob = import_blob(Wh, qw, sw, shp.N, shp.K, shp.r, shp.g)
+    y = B.linear(dev_bf16(L.x_bits), Qt, blob, shp.N, shp.r, shp.g)
+    torch.cuda.synchronize()
+    check_output(O.from_bf16_bits(host_bf16_bits(y)), ref["y32"], tol=1e-2)
+
+
+def test_deterministic_and_empty():
+    L, (Wh, qw, sw), _ = layer_with_oracle(I.SMALL)
+    shp = I.SMALL
+    Qt = B.prepare_rotation(dev(L.Q32))
+    blob = import_blob(Wh, qw, sw, shp.N, shp.K, shp.r, shp.g)
+    x = dev_bf16(L.x_bits)
+    y1 = B.linear(x, Qt, blob, shp.N, shp.r, shp.g)
+    y2 = B.linear(x, Qt, blob, shp.N, shp.r, shp.g)
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y2)
+    y0 = B.linear(x[:0], Qt, blob, shp.N, shp.r, shp.g)          # M == 0: a no-op
+    assert y0.shape == (0, shp.N)
+    # out-of-bounds canary: outputs sit inside a larger buffer that must stay untouched
+    M = 100
+    big = torch.full((M + 2, shp.N), 1.0, dtype=torch.bfloat16, device="cuda")
+    B.linear(x[:M], Qt, blob, shp.N, shp.r, shp.g, out=big[1:M + 1])
+    torch.cuda.synchronize()
+    assert torch.all(big[0] == 1.0) and torch.all(big[M + 1] == 1.0)
+    assert torch.equal(big[1:M + 1], y1[:M])
