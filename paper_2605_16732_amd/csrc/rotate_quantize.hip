@@ -3,215 +3,311 @@
 // equation of Section 4.2 and the quantizer of Section 3 of the paper).
 //
 // Orientation.  The product is computed transposed, D[channel][token] =
-// sum_k Qt[channel][k] x[token][k], so both operands stream K-contiguous rows.
-// Rotated channels are tiled relative to the split point r: tiles [0, n_hi) cover the
-// bf16 channels [0, r), the rest cover [r, K) starting at r, so a quantization group
-// (g | 128) never straddles a tile.
+// sum_k Qt[channel][k] x[token][k]: both operands stream K-contiguous rows, and in the
+// 32x32 MFMA accumulator layout a lane then owns ONE token and 4 consecutive rotated
+// channels per register quad.  A wave computes 128 channels x 64 tokens, so every
+// quantization group (32, 64 or 128 channels of one token) lives in one lane pair
+// (l, l^32): the absmax is an in-lane max plus one cross-lane exchange, the codes are
+// packed in registers, and nothing is staged through LDS after the main loop.
+//
+// Channel tiling.  Waves own 128 "virtual" channels: the bf16 part [0, r) is padded to a
+// multiple of 128, the 4-bit part [r, K) follows, so groups never straddle a wave.
+//
+// Main loop.  Operand tiles go HBM -> LDS directly (global_load_lds, 16 B per lane),
+// NBUF stages deep, with an XOR swizzle applied on the global side so that the 16-byte
+// MFMA operand reads of 16 consecutive rows are bank-conflict free.
 #include "dirotq_internal.h"
 
 namespace dirotq {
 
-constexpr int BC = 128;        // rotated channels per workgroup tile
-constexpr int BT = 128;        // tokens per workgroup tile
-constexpr int BK = 64;         // contraction step staged in LDS
-constexpr int NTHREADS = 256;  // 4 waves as 2 (channels) x 2 (tokens), 64x64 each
-constexpr int STAGE_LD = BC + 4;  // floats per token row of the epilogue staging tile
-constexpr int OPER_BYTES = BC * BK * 2;                      // one operand tile, bf16
-constexpr int SMEM_LOOP = 4 * OPER_BYTES;                    // A,B double-buffered
-constexpr int SMEM_EPI = BT * STAGE_LD * 4;
-constexpr int SMEM_BYTES = SMEM_LOOP > SMEM_EPI ? SMEM_LOOP : SMEM_EPI;
+typedef __attribute__((address_space(3))) void lds_void;
+#ifndef DIROTQ_RQ_AUX
+#define DIROTQ_RQ_AUX 0
+#endif
 
-// Tiles are [128 rows][64 bf16] = 8 chunks of 16 B per row; chunk c of row r lives at
-// slot c ^ (r & 7) so that the 16-B MFMA operand reads of 16 consecutive rows hit 16
-// different bank groups.
-__device__ __forceinline__ int tile_off(int row, int chunk) {  // in bf16 elements
-  return row * BK + ((chunk ^ (row & 7)) << 3);
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  // gfx9 s_waitcnt: vmcnt = imm[3:0] | imm[15:14]<<4, expcnt = imm[6:4], lgkmcnt = imm[11:8]
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
-__global__ __launch_bounds__(NTHREADS, 2) void rotate_quantize_kernel(
+template <int WGC, int WGT, int BK, int NBUF>
+struct RQ {
+  static constexpr int WAVE_C = 128, WAVE_T = 64;          // wave tile: channels x tokens
+  static constexpr int TC = WGC * WAVE_C, TT = WGT * WAVE_T;
+  static constexpr int NW = WGC * WGT, NT = NW * 64;
+  static constexpr int ROWB = BK * 2;                      // bytes per LDS row
+  static constexpr int CPR = ROWB / 16;                    // 16-B chunks per row
+  static constexpr int STAGE_BYTES = (TC + TT) * ROWB;
+  static constexpr int IPW = (TC + TT) * CPR / 64 / NW;    // load instructions per wave per stage
+  static constexpr int SMEM = NBUF * STAGE_BYTES;
+  static_assert((TC + TT) * CPR % (64 * NW) == 0, "loads must divide evenly over waves");
+  static_assert(BK == 32 || BK == 64, "BK");
+  static_assert(NBUF >= 2 && NBUF <= 4, "NBUF");
+
+  // chunk c of row `row` is stored in 16-B slot c ^ swz(row)
+  // (LDS has 64 banks: a 16-byte read is served 16 lanes per cycle, so 16 consecutive rows
+  // must land in 16 different 16-byte slots of a 256-byte bank line)
+  __device__ static __forceinline__ int swz(int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
+};
+
+template <int WGC, int WGT, int BK, int NBUF>
+__global__ __launch_bounds__(WGC* WGT * 64, 2) void rotate_quantize_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ Qt, int M, int K, int r, int g,
-    uint16_t* __restrict__ xh, uint8_t* __restrict__ xl, uint16_t* __restrict__ sx, int n_hi, int n_ct,
+    uint16_t* __restrict__ xh, uint8_t* __restrict__ xl, uint16_t* __restrict__ sx, int r_pad, int Kv, int n_ct,
     int n_tt, int per_xcd) {
+  using C = RQ<WGC, WGT, BK, NBUF>;
   extern __shared__ __align__(16) unsigned char smem[];
-  uint16_t* As = (uint16_t*)smem;                       // [2][BC*BK]
-  uint16_t* Bs = (uint16_t*)(smem + 2 * OPER_BYTES);    // [2][BT*BK]
 
   // consecutive workgroup ids go to different XCDs; give each XCD a contiguous run of tiles
   const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (logical >= n_ct * n_tt) return;
-  const int tt = logical % n_tt, ct = logical / n_tt;
-  const bool hi = ct < n_hi;
-  const int c0 = hi ? ct * BC : r + (ct - n_hi) * BC;
-  const int c_lim = hi ? r : K;
-  const int m0 = tt * BT;
+  // within an XCD's run, sweep GC channel tiles per token tile so that co-resident
+  // workgroups share both operands through the XCD's L2
+  constexpr int GC = 4;
+  const int grp = logical / (GC * n_tt), in_grp = logical % (GC * n_tt);
+  const int gc = min(n_ct - grp * GC, GC);
+  const int ct = grp * GC + in_grp % gc, tt = in_grp / gc;
+  const int m0 = tt * C::TT;
 
   const int t = threadIdx.x, l = t & 63, w = t >> 6;
-  const int wc = w & 1, wt = w >> 1;
+  const int wc = w % WGC, wt = w / WGC;
 
-  // global -> register staging: 4 chunks of 16 B per operand per thread
-  const int lrow = t >> 3, lchunk = t & 7;
-  const uint16_t* ga[4];
-  const uint16_t* gb[4];
+  // ---- per-lane source pointers of this wave's load instructions --------------------
+  // instruction i of wave w fills LDS bytes [(w*IPW+i)*1024, +1024) of a stage: rows are
+  // the TC channel rows followed by the TT token rows.
+  const uint16_t* gsrc[C::IPW];
 #pragma unroll
-  for (int i = 0; i < 4; i++) {
-    int c = min(c0 + lrow + 32 * i, c_lim - 1);
-    int m = min(m0 + lrow + 32 * i, M - 1);
-    ga[i] = Qt + (size_t)c * K + lchunk * 8;
-    gb[i] = x + (size_t)m * K + lchunk * 8;
+  for (int i = 0; i < C::IPW; i++) {
+    const int ci = (w * C::IPW + i) * 64 + l;               // chunk index within the stage
+    const int row = ci / C::CPR, phys = ci % C::CPR;
+    const int logical_chunk = phys ^ C::swz(row);
+    const uint16_t* base;
+    if (row < C::TC) {
+#ifdef DIROTQ_EXP_SAMETILE
+      const int v = row;
+#else
+      const int v = ct * C::TC + row;                       // virtual channel
+#endif
+      int ch = v < r_pad ? min(v, r - 1) : min(r + (v - r_pad), K - 1);
+      ch = max(ch, 0);
+      base = Qt + (size_t)ch * K;
+    } else {
+#ifdef DIROTQ_EXP_SAMETILE
+      base = x + (size_t)min(row - C::TC, M - 1) * K;
+#else
+      base = x + (size_t)min(m0 + row - C::TC, M - 1) * K;
+#endif
+    }
+    gsrc[i] = base + logical_chunk * 8;
   }
-  uint4 ra[4], rb[4];
-  auto gload = [&](int k0) {
-    const bool ok = k0 + lchunk * 8 < K;
+  auto issue_part = [&](int kt, int buf, int part, int nparts) {
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-      ra[i] = ok ? *(const uint4*)(ga[i] + k0) : make_uint4(0, 0, 0, 0);
-      rb[i] = ok ? *(const uint4*)(gb[i] + k0) : make_uint4(0, 0, 0, 0);
-    }
+    for (int i = 0; i < C::IPW; i++)
+      if (i * nparts / C::IPW == part)
+        __builtin_amdgcn_global_load_lds((const void*)(gsrc[i] + kt * BK),
+                                         (lds_void*)(smem + buf * C::STAGE_BYTES + (w * C::IPW + i) * 1024), 16,
+                                         0, DIROTQ_RQ_AUX);
   };
-  auto sstore = [&](int buf) {
+  auto issue = [&](int kt, int buf) {
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
-      int row = lrow + 32 * i;
-      *(uint4*)(As + buf * (BC * BK) + tile_off(row, lchunk)) = ra[i];
-      *(uint4*)(Bs + buf * (BT * BK) + tile_off(row, lchunk)) = rb[i];
-    }
+    for (int i = 0; i < C::IPW; i++)
+      __builtin_amdgcn_global_load_lds((const void*)(gsrc[i] + kt * BK),
+                                       (lds_void*)(smem + buf * C::STAGE_BYTES + (w * C::IPW + i) * 1024), 16, 0,
+                                       DIROTQ_RQ_AUX);
   };
 
-  f32x16 acc[2][2];
+  f32x16 acc[4][2];
 #pragma unroll
-  for (int i = 0; i < 2; i++)
+  for (int i = 0; i < 4; i++)
 #pragma unroll
     for (int j = 0; j < 2; j++)
 #pragma unroll
       for (int v = 0; v < 16; v++) acc[i][j][v] = 0.0f;
 
-  const int nk = (K + BK - 1) / BK;
-  gload(0);
-  sstore(0);
-  __syncthreads();
-  for (int kt = 0; kt < nk; kt++) {
-    const int buf = kt & 1;
-    if (kt + 1 < nk) gload((kt + 1) * BK);
-    const uint16_t* Ab = As + buf * (BC * BK);
-    const uint16_t* Bb = Bs + buf * (BT * BK);
+  // operand read offsets (bytes within a stage) for k-step 0; k-step ks flips chunk bits
+  int offA[4], offB[2];
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ks++) {
-      bf16x8 a[2], b[2];
+  for (int i = 0; i < 4; i++) offA[i] = (wc * 128 + i * 32 + (l & 31)) * C::ROWB;
+#pragma unroll
+  for (int j = 0; j < 2; j++) offB[j] = (C::TC + wt * 64 + j * 32 + (l & 31)) * C::ROWB;
+  const int swzA = C::swz(l & 31), swzB = C::swz(l & 31);   // tile bases are multiples of 32 rows
+
+  const int nk = K / BK;                                    // the launcher guarantees K % BK == 0
+#pragma unroll
+  for (int s = 0; s < NBUF - 1; s++)
+    if (s < nk) issue(s, s);
+
+  for (int kt = 0; kt < nk; kt++) {
+    const int rem = nk - 1 - kt;                            // stages issued after stage kt
+    if (NBUF >= 4 && rem >= 2) wait_vmcnt<2 * C::IPW>();
+    else if (NBUF >= 3 && rem >= 1) wait_vmcnt<1 * C::IPW>();
+    else wait_vmcnt<0>();
+#ifndef DIROTQ_EXP_NOBAR
+    __syncthreads();
+#endif
+    const bool more = kt + NBUF - 1 < nk;
+#if !defined(DIROTQ_EXP_NOLOAD) && !defined(DIROTQ_RQ_SPREAD)
+    if (more) issue(kt + NBUF - 1, (kt + NBUF - 1) % NBUF);
+#endif
+    const unsigned char* sb = smem + (kt % NBUF) * C::STAGE_BYTES;
+#ifdef DIROTQ_RQ_PREFETCH
+    // operands of k-step ks+1 are fetched from LDS while the MFMAs of k-step ks run
+    bf16x8 a[2][4], b[2][2];
+    auto lds_fetch = [&](int ks, int slot) {
       const int chunk = 2 * ks + (l >> 5);
 #pragma unroll
-      for (int i = 0; i < 2; i++) {
-        int ra_ = wc * 64 + i * 32 + (l & 31);
-        int rb_ = wt * 64 + i * 32 + (l & 31);
-        a[i] = *(const bf16x8*)(Ab + tile_off(ra_, chunk));
-        b[i] = *(const bf16x8*)(Bb + tile_off(rb_, chunk));
-      }
+      for (int i = 0; i < 4; i++) a[slot][i] = *(const bf16x8*)(sb + offA[i] + ((chunk ^ swzA) << 4));
 #pragma unroll
-      for (int i = 0; i < 2; i++)
+      for (int j = 0; j < 2; j++) b[slot][j] = *(const bf16x8*)(sb + offB[j] + ((chunk ^ swzB) << 4));
+    };
+    lds_fetch(0, 0);
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ks++) {
+      if (ks + 1 < BK / 16) lds_fetch(ks + 1, (ks + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads ahead of this k-step's MFMAs
+#pragma unroll
+      for (int i = 0; i < 4; i++)
+#pragma unroll
+        for (int j = 0; j < 2; j++)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][i], b[ks & 1][j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#else
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ks++) {
+      const int chunk = 2 * ks + (l >> 5);
+      bf16x8 a[4], b[2];
+#pragma unroll
+      for (int i = 0; i < 4; i++) a[i] = *(const bf16x8*)(sb + offA[i] + ((chunk ^ swzA) << 4));
+#pragma unroll
+      for (int j = 0; j < 2; j++) b[j] = *(const bf16x8*)(sb + offB[j] + ((chunk ^ swzB) << 4));
+#ifdef DIROTQ_RQ_SPREAD
+      if (more) issue_part(kt + NBUF - 1, (kt + NBUF - 1) % NBUF, ks, BK / 16);
+#endif
+#pragma unroll
+      for (int i = 0; i < 4; i++)
 #pragma unroll
         for (int j = 0; j < 2; j++)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) sstore(buf ^ 1);
-    __syncthreads();
+#endif
   }
 
-  // ---- epilogue: accumulators -> LDS as [token][channel] fp32 --------------------
-  float* stage = (float*)smem;
-#pragma unroll
-  for (int i = 0; i < 2; i++)
+  // ---- epilogue, in registers ------------------------------------------------------
+  const int vb = ct * C::TC + wc * 128;                     // first virtual channel of this wave
+  if (vb >= Kv) return;
+  const int h = l >> 5;
+  if (vb < r_pad) {
+    // 16-bit part: 4 consecutive channels per register quad -> one 8-byte store
 #pragma unroll
     for (int j = 0; j < 2; j++) {
-      const int token = wt * 64 + j * 32 + (l & 31);
+      const int m = m0 + wt * 64 + j * 32 + (l & 31);
+#pragma unroll
+      for (int i = 0; i < 4; i++)
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+          const int c = vb + i * 32 + 8 * q + 4 * h;
+          if (c < r && m < M) {
+            uint2 o;
+            o.x = f32_to_bf16_bits(acc[i][j][4 * q]) | ((uint32_t)f32_to_bf16_bits(acc[i][j][4 * q + 1]) << 16);
+            o.y = f32_to_bf16_bits(acc[i][j][4 * q + 2]) | ((uint32_t)f32_to_bf16_bits(acc[i][j][4 * q + 3]) << 16);
+            *(uint2*)(xh + (size_t)m * r + c) = o;
+          }
+        }
+    }
+    return;
+  }
+  const int cl0 = vb - r_pad;                               // first 4-bit channel of this wave
+  const int KL = K - r;
+  const size_t xl_ld = (size_t)KL / 2;
+  const int gi_tiles = g >> 5;                              // 32-channel MFMA tiles per group: 1, 2, 4
+#pragma unroll
+  for (int j = 0; j < 2; j++) {
+    const int m = m0 + wt * 64 + j * 32 + (l & 31);
+    // absmax of each 32-channel tile over the lane pair, then combined per group
+    float tmax[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      float a = 0.0f;
+#pragma unroll
+      for (int v = 0; v < 16; v++) a = fmaxf(a, fabsf(acc[i][j][v]));
+      tmax[i] = fmaxf(a, __shfl_xor(a, 32));
+    }
+    if (gi_tiles == 2) {
+      tmax[0] = tmax[1] = fmaxf(tmax[0], tmax[1]);
+      tmax[2] = tmax[3] = fmaxf(tmax[2], tmax[3]);
+    } else if (gi_tiles == 4) {
+      tmax[0] = tmax[1] = tmax[2] = tmax[3] = fmaxf(fmaxf(tmax[0], tmax[1]), fmaxf(tmax[2], tmax[3]));
+    }
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const int cl = cl0 + i * 32;                          // first 4-bit channel of this tile
+      const bool valid = cl < KL && m < M;
+      uint16_t sbits;
+      const float sf = group_scale(tmax[i], sbits);
+      const float inv = group_inv(sf);
+      if (valid && h == 0 && (i % gi_tiles) == 0) sx[(size_t)(cl / g) * M + m] = sbits;
+      // this lane's 16 codes: quad q covers channels cl + 8q + 4h .. +3 -> one 16-bit piece
+      uint32_t piece[4];
 #pragma unroll
       for (int q = 0; q < 4; q++) {
-        const int ch = wc * 64 + i * 32 + 8 * q + 4 * (l >> 5);
-        float4 v = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
-                               acc[i][j][4 * q + 3]);
-        *(float4*)(stage + token * STAGE_LD + ch) = v;
+        piece[q] = (uint32_t)(quant_code(acc[i][j][4 * q], inv) & 0xF) |
+                   (uint32_t)(quant_code(acc[i][j][4 * q + 1], inv) & 0xF) << 4 |
+                   (uint32_t)(quant_code(acc[i][j][4 * q + 2], inv) & 0xF) << 8 |
+                   (uint32_t)(quant_code(acc[i][j][4 * q + 3], inv) & 0xF) << 12;
       }
-    }
-  __syncthreads();
-
-  if (hi) {
-    // bf16 part: one unit = (token, 32 channels) -> 64 contiguous bytes of xh
-    for (int u = t; u < BT * (BC / 32); u += NTHREADS) {
-      const int token = u & (BT - 1), chk = u >> 7;
-      const int c = c0 + chk * 32, m = m0 + token;
-      if (c >= c_lim || m >= M) continue;
-      const float* src = stage + token * STAGE_LD + chk * 32;
-      uint16_t* dst = xh + (size_t)m * r + c;
-#pragma unroll
-      for (int p = 0; p < 4; p++) {
-        float4 v0 = *(const float4*)(src + 8 * p), v1 = *(const float4*)(src + 8 * p + 4);
-        uint4 o;
-        o.x = f32_to_bf16_bits(v0.x) | ((uint32_t)f32_to_bf16_bits(v0.y) << 16);
-        o.y = f32_to_bf16_bits(v0.z) | ((uint32_t)f32_to_bf16_bits(v0.w) << 16);
-        o.z = f32_to_bf16_bits(v1.x) | ((uint32_t)f32_to_bf16_bits(v1.y) << 16);
-        o.w = f32_to_bf16_bits(v1.z) | ((uint32_t)f32_to_bf16_bits(v1.w) << 16);
-        *(uint4*)(dst + 8 * p) = o;
-      }
-    }
-  } else {
-    // INT4 part: one unit = (token, group of g channels)
-    const int ng = BC / g;
-    const size_t xl_ld = (size_t)(K - r) / 2;
-    for (int u = t; u < BT * ng; u += NTHREADS) {
-      const int token = u & (BT - 1), grp = u >> 7;
-      const int cl = (c0 - r) + grp * g;   // first 4-bit channel of the group
-      const int m = m0 + token;
-      if (c0 + grp * g >= c_lim || m >= M) continue;
-      const float* src = stage + token * STAGE_LD + grp * g;
-      float amax = 0.0f;
-      for (int p = 0; p < g; p += 4) {
-        float4 v = *(const float4*)(src + p);
-        amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
-      }
-      uint16_t sbits;
-      const float sf = group_scale(amax, sbits);
-      const float inv = group_inv(sf);
-      sx[(size_t)(cl / g) * M + m] = sbits;
-      uint8_t* dst = xl + (size_t)m * xl_ld + cl / 2;
-      for (int p = 0; p < g; p += 32) {
-        uint32_t o[4];
-#pragma unroll
-        for (int d = 0; d < 4; d++) {
-          float4 v0 = *(const float4*)(src + p + 8 * d), v1 = *(const float4*)(src + p + 8 * d + 4);
-          uint32_t wv = 0;
-          wv |= (uint32_t)(quant_code(v0.x, inv) & 0xF);
-          wv |= (uint32_t)(quant_code(v0.y, inv) & 0xF) << 4;
-          wv |= (uint32_t)(quant_code(v0.z, inv) & 0xF) << 8;
-          wv |= (uint32_t)(quant_code(v0.w, inv) & 0xF) << 12;
-          wv |= (uint32_t)(quant_code(v1.x, inv) & 0xF) << 16;
-          wv |= (uint32_t)(quant_code(v1.y, inv) & 0xF) << 20;
-          wv |= (uint32_t)(quant_code(v1.z, inv) & 0xF) << 24;
-          wv |= (uint32_t)(quant_code(v1.w, inv) & 0xF) << 28;
-          o[d] = wv;
-        }
-        *(uint4*)(dst + p / 2) = make_uint4(o[0], o[1], o[2], o[3]);
-      }
+      const uint32_t P0 = piece[0] | (piece[1] << 16), P1 = piece[2] | (piece[3] << 16);
+      // lane h=0 keeps dwords 0,1 of the tile's 16 bytes, lane h=1 dwords 2,3
+      const uint32_t recv = __shfl_xor(h ? P0 : P1, 32);
+      const uint32_t lo = h ? recv : P0, hi = h ? P1 : recv;
+      uint2 o;
+      o.x = (lo & 0xFFFFu) | (hi << 16);
+      o.y = (lo >> 16) | (hi & 0xFFFF0000u);
+      if (valid) *(uint2*)(xl + (size_t)m * xl_ld + cl / 2 + 8 * h) = o;
     }
   }
 }
 
-int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g, uint16_t* xh,
-                           uint8_t* xl, uint16_t* sx, hipStream_t s) {
-  const int n_hi = (r + BC - 1) / BC;
-  const int n_lo = (K - r + BC - 1) / BC;
-  const int n_ct = n_hi + n_lo;
-  const int n_tt = (M + BT - 1) / BT;
+template <int WGC, int WGT, int BK, int NBUF>
+static int launch_cfg(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g, uint16_t* xh,
+                      uint8_t* xl, uint16_t* sx, hipStream_t s) {
+  using C = RQ<WGC, WGT, BK, NBUF>;
+  const int r_pad = (r + 127) / 128 * 128;
+  const int Kv = r_pad + (K - r + 127) / 128 * 128;
+  const int n_ct = (Kv + C::TC - 1) / C::TC;
+  const int n_tt = (M + C::TT - 1) / C::TT;
   const long n_blocks = (long)n_ct * n_tt;
   const int per_xcd = (int)((n_blocks + 7) / 8);
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)rotate_quantize_kernel,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
+    hipError_t e = hipFuncSetAttribute((const void*)rotate_quantize_kernel<WGC, WGT, BK, NBUF>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
     if (e != hipSuccess) return hip_failed(e);
     attr_done = true;
   }
-  hipLaunchKernelGGL(rotate_quantize_kernel, dim3(per_xcd * 8), dim3(NTHREADS), SMEM_BYTES, s, x, Qt, M, K,
-                     r, g, xh, xl, sx, n_hi, n_ct, n_tt, per_xcd);
+  hipLaunchKernelGGL((rotate_quantize_kernel<WGC, WGT, BK, NBUF>), dim3(per_xcd * 8), dim3(C::NT), C::SMEM, s, x,
+                     Qt, M, K, r, g, xh, xl, sx, r_pad, Kv, n_ct, n_tt, per_xcd);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? DIROTQ_OK : hip_failed(e);
+}
+
+int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g, uint16_t* xh,
+                           uint8_t* xl, uint16_t* sx, hipStream_t s) {
+  // Large problems: 256 x 256 workgroup tiles (8 waves); medium: 256 channels x 128 tokens
+  // (4 waves); small: 128 x 128 (2 waves), so that the grid still covers the chip.
+  const int r_pad = (r + 127) / 128 * 128;
+  const int Kv = r_pad + (K - r + 127) / 128 * 128;
+  const long n_tc256 = (Kv + 255) / 256;
+  const long big_tiles = n_tc256 * ((M + 255) / 256);    // 256 channels x 256 tokens
+  const long mid_tiles = n_tc256 * ((M + 127) / 128);    // 256 channels x 128 tokens
+#ifdef DIROTQ_RQ_FORCE   // build-time tuning aid: -DDIROTQ_RQ_FORCE=WGC,WGT,BK,NBUF
+  return launch_cfg<DIROTQ_RQ_FORCE>(x, Qt, M, K, r, g, xh, xl, sx, s);
+#endif
+  if (K % 64 != 0) return launch_cfg<1, 2, 32, 4>(x, Qt, M, K, r, g, xh, xl, sx, s);
+  if (big_tiles >= 200) return launch_cfg<2, 4, 64, 2>(x, Qt, M, K, r, g, xh, xl, sx, s);
+  if (mid_tiles >= 100) return launch_cfg<2, 2, 64, 2>(x, Qt, M, K, r, g, xh, xl, sx, s);
+  return launch_cfg<1, 2, 64, 2>(x, Qt, M, K, r, g, xh, xl, sx, s);
 }
 
 }  // namespace dirotq

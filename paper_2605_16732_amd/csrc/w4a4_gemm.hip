@@ -1,30 +1,43 @@
 // Kernel B: y = x_h W'_h^T + sum_j s_x[:,j] s_w[:,j]^T * (q_x,j q_w,j^T)
 // (forward-computation equation of Section 4.2 of the paper).
 //
-// The INT4 codes are unpacked once per workgroup on their way into LDS: a nibble is
-// moved to the high half of a byte, so the i8 MFMA operand holds 16 q and the int32
-// group dot is 256 I exactly (|256 I| <= 256 * 49 * 128 < 2^31); the factor 2^-8 is
-// folded into the fp32 weight scale (exact).  Even and odd channels of an 8-channel
-// dword land in different operand registers; both operands use the same permutation,
-// so the dot product is unchanged.
+// Orientation.  D[n][token]: output channels on the MFMA row axis, tokens on the column
+// axis, so a lane owns one token and 4 consecutive output channels per register quad
+// (one 8-byte bf16 store).  Workgroup tile 256 n x 256 tokens, 8 waves as 2 (n) x 4
+// (tokens), each 128 n x 64 tokens.
+//
+// Integer part.  INT4 codes are unpacked once per workgroup on their way into LDS: a
+// nibble is moved to the high half of a byte, so the i8 MFMA operand holds 16 q and the
+// int32 group dot is 256 I exactly (|256 I| <= 256 * 49 * 128 < 2^31).  Even and odd
+// channels of an 8-channel dword land in different operand registers; both operands use
+// the same permutation, so the dot product is unchanged.
+//
+// Dequantisation.  The per-group scale product P[n][token] = s_w[n,j] * s_x[token,j] is an
+// outer product of fp16 vectors: it is produced exactly (fp16 x fp16 fits fp32) by one
+// fp16 MFMA whose operands carry the scales in k-slot 0 and zeros elsewhere, which
+// leaves the vector ALU one convert and one fma per accumulator and group:
+// acc += float(256 I) * P.  The common factor 2^-8 is applied once at the end (exact),
+// before the 16-bit branch is accumulated on top by bf16 MFMAs.
 #include "dirotq_internal.h"
 
 namespace dirotq {
 
-constexpr int BM = 128;         // tokens per workgroup tile
-constexpr int BN = 128;         // output channels per workgroup tile
+constexpr int TN = 256;         // output channels per workgroup tile
+constexpr int TM = 256;         // tokens per workgroup tile
 constexpr int BKQ = 128;        // 4-bit channels per LDS stage (one 128-byte i8 row)
-constexpr int NTHREADS = 256;   // 4 waves as 2 (tokens) x 2 (outputs), 64x64 each
-constexpr int STAGE_LD = BN + 4;
-constexpr int OPER_BYTES = BM * BKQ;                 // one i8 operand tile (= one bf16 [128][64] tile)
-constexpr int SCALE_BYTES = 4 * 128 * 4;             // up to 4 groups x 128 rows, fp32
-constexpr int SMEM_LOOP = 4 * OPER_BYTES + 4 * SCALE_BYTES;
-constexpr int SMEM_EPI = BM * STAGE_LD * 4;
-constexpr int SMEM_BYTES = SMEM_LOOP > SMEM_EPI ? SMEM_LOOP : SMEM_EPI;
+constexpr int NTHREADS = 512;   // 8 waves as 2 (n) x 4 (tokens), 128 n x 64 tokens each
+constexpr int ROWS = TN + TM;
+constexpr int STAGE_BYTES = ROWS * 128;              // i8 [512 rows][128 B] (= bf16 [512][64])
+constexpr int SCALE_OFF = 2 * STAGE_BYTES;           // u32 [2 bufs][4 groups][512 rows]: fp16 scale, zero-extended
+constexpr int SCALE_BUF_BYTES = 4 * ROWS * 4;
+constexpr int ZERO_OFF = SCALE_OFF + 2 * SCALE_BUF_BYTES;
+constexpr int SMEM_BYTES = ZERO_OFF + 256;
 
-// [128 rows][128 B] tiles, 16-B chunk c of row r stored at slot c ^ (r & 7)
+// [rows][128 B] tiles, 16-B chunk c of row r stored at slot c ^ ((r >> 1) & 7): LDS has
+// 64 banks and serves 16-byte accesses 16 lanes per cycle, so 16 consecutive rows must
+// fall into 16 different 16-byte slots of a 256-byte bank line.
 __device__ __forceinline__ int tile_off_bytes(int row, int chunk) {
-  return row * 128 + ((chunk ^ (row & 7)) << 4);
+  return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
 }
 
 // 8 nibbles of a dword -> two dwords of i8 holding 16*q: even channels, odd channels
@@ -40,92 +53,64 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
     const uint16_t* __restrict__ bias, int M, int N, int K, int r, void* __restrict__ y, int n_mt, int n_nt,
     int per_xcd) {
   extern __shared__ __align__(16) unsigned char smem[];
-  unsigned char* As = smem;                      // [2][OPER_BYTES]
-  unsigned char* Bs = smem + 2 * OPER_BYTES;     // [2][OPER_BYTES]
-  float* sxs = (float*)(smem + 4 * OPER_BYTES);  // [2][4][128]
-  float* sws = sxs + 2 * 4 * 128;                // [2][4][128]
 
   const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (logical >= n_mt * n_nt) return;
-  const int mt = logical % n_mt, nt = logical / n_mt;
-  const int m0 = mt * BM, n0 = nt * BN;
+  // within an XCD's run, sweep GN output tiles per token tile (shared operands stay in L2)
+  constexpr int GN = 4;
+  const int grp = logical / (GN * n_mt), in_grp = logical % (GN * n_mt);
+  const int gn = min(n_nt - grp * GN, GN);
+  const int nt = grp * GN + in_grp % gn, mt = in_grp / gn;
+  const int m0 = mt * TM, n0 = nt * TN;
 
   const int t = threadIdx.x, l = t & 63, w = t >> 6;
-  const int wm = w & 1, wn = w >> 1;
+  const int wn = w & 1, wt = w >> 1;
+  const int h = l >> 5;
   const int KL = K - r;            // number of 4-bit channels
   const int G = KL / GS;
   constexpr int GPS = BKQ / GS;    // groups per stage
-  constexpr int MPG = GS / 32;     // MFMAs (k = 32) per group
+  constexpr int MPG = GS / 32;     // i8 MFMAs (k = 32) per group
 
-  f32x16 acc[2][2];
+  if (t < 64) ((uint32_t*)(smem + ZERO_OFF))[t] = 0u;
+
+  f32x16 acc[4][2];
 #pragma unroll
-  for (int i = 0; i < 2; i++)
+  for (int i = 0; i < 4; i++)
 #pragma unroll
     for (int j = 0; j < 2; j++)
 #pragma unroll
       for (int v = 0; v < 16; v++) acc[i][j][v] = 0.0f;
 
-  // ---- 16-bit branch: acc = x_h W'_h^T, bf16 MFMA, 64 channels per stage ---------
-  if (r > 0) {
-    const int lrow = t >> 3, lchunk = t & 7;
-    for (int k0 = 0; k0 < r; k0 += 64) {
-      const bool ok = k0 + lchunk * 8 < r;
+  // operand rows of this lane: A = weights (rows 0..255 of a stage), B = tokens (256..511)
+  int rowA[4], rowB[2];
 #pragma unroll
-      for (int i = 0; i < 4; i++) {
-        const int row = lrow + 32 * i;
-        const int m = min(m0 + row, M - 1), n = min(n0 + row, N - 1);
-        uint4 va = ok ? *(const uint4*)(xh + (size_t)m * r + k0 + lchunk * 8) : make_uint4(0, 0, 0, 0);
-        uint4 vb = ok ? *(const uint4*)(wh + (size_t)n * r + k0 + lchunk * 8) : make_uint4(0, 0, 0, 0);
-        *(uint4*)(As + tile_off_bytes(row, lchunk)) = va;
-        *(uint4*)(Bs + tile_off_bytes(row, lchunk)) = vb;
-      }
-      __syncthreads();
+  for (int i = 0; i < 4; i++) rowA[i] = wn * 128 + i * 32 + (l & 31);
 #pragma unroll
-      for (int ks = 0; ks < 4; ks++) {
-        bf16x8 a[2], b[2];
-        const int chunk = 2 * ks + (l >> 5);
-#pragma unroll
-        for (int i = 0; i < 2; i++) {
-          a[i] = *(const bf16x8*)(As + tile_off_bytes(wm * 64 + i * 32 + (l & 31), chunk));
-          b[i] = *(const bf16x8*)(Bs + tile_off_bytes(wn * 64 + i * 32 + (l & 31), chunk));
-        }
-#pragma unroll
-        for (int i = 0; i < 2; i++)
-#pragma unroll
-          for (int j = 0; j < 2; j++)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-      }
-      __syncthreads();
-    }
-  }
+  for (int j = 0; j < 2; j++) rowB[j] = TN + wt * 64 + j * 32 + (l & 31);
+  const int swz = ((l & 31) >> 1) & 7;                 // tile bases are multiples of 32 rows
 
   // ---- 4-bit branch ---------------------------------------------------------------
   if (KL > 0) {
-    const size_t ldq = (size_t)KL / 2;       // packed bytes per row
-    const int prow = t >> 2, pchunk = t & 3; // 2 rows x one 16-B packed chunk per operand per thread
-    const uint8_t* ga[2];
-    const uint8_t* gb[2];
+    const size_t ldq = (size_t)KL / 2;        // packed bytes per row
+    const int prow = t >> 2, pchunk = t & 3;  // 4 rows (stride 128) x one 16-B packed chunk per thread
+    const uint8_t* gq[4];
 #pragma unroll
-    for (int i = 0; i < 2; i++) {
-      ga[i] = xl + (size_t)min(m0 + prow + 64 * i, M - 1) * ldq + pchunk * 16;
-      gb[i] = wq + (size_t)min(n0 + prow + 64 * i, N - 1) * ldq + pchunk * 16;
+    for (int i = 0; i < 4; i++) {
+      const int row = prow + 128 * i;
+      gq[i] = (row < TN ? wq + (size_t)min(n0 + row, N - 1) * ldq : xl + (size_t)min(m0 + row - TN, M - 1) * ldq) +
+              pchunk * 16;
     }
-    // scale staging: threads 0..127 own a token, 128..255 an output channel
-    const bool is_x = t < 128;
-    const int srow = t & 127;
-    const uint16_t* gs = is_x ? sx + min(m0 + srow, M - 1) : sw + min(n0 + srow, N - 1);
-    const size_t s_ld = is_x ? (size_t)M : (size_t)N;
-    const float s_mul = is_x ? 1.0f : 0.00390625f;   // 2^-8 undoes the two 16x operand factors
+    // scale staging: thread t owns row t of the stage (weights then tokens)
+    const uint16_t* gs = t < TN ? sw + min(n0 + t, N - 1) : sx + min(m0 + t - TN, M - 1);
+    const size_t s_ld = t < TN ? (size_t)N : (size_t)M;
 
-    uint4 ra[2], rb[2];
+    uint4 rq[4];
     uint16_t rs[GPS];
     auto gload = [&](int st) {
       const bool ok = st * BKQ + pchunk * 32 < KL;
 #pragma unroll
-      for (int i = 0; i < 2; i++) {
-        ra[i] = ok ? *(const uint4*)(ga[i] + (size_t)st * (BKQ / 2)) : make_uint4(0, 0, 0, 0);
-        rb[i] = ok ? *(const uint4*)(gb[i] + (size_t)st * (BKQ / 2)) : make_uint4(0, 0, 0, 0);
-      }
+      for (int i = 0; i < 4; i++)
+        rq[i] = ok ? *(const uint4*)(gq[i] + (size_t)st * (BKQ / 2)) : make_uint4(0, 0, 0, 0);
 #pragma unroll
       for (int jj = 0; jj < GPS; jj++) {
         const int j = st * GPS + jj;
@@ -133,27 +118,32 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
       }
     };
     auto sstore = [&](int buf) {
+      unsigned char* sb = smem + buf * STAGE_BYTES;
 #pragma unroll
-      for (int i = 0; i < 2; i++) {
-        const int row = prow + 64 * i;
+      for (int i = 0; i < 4; i++) {
+        const int row = prow + 128 * i;
         uint4 e, o;
-        unpack8(ra[i].x, e.x, o.x);
-        unpack8(ra[i].y, e.y, o.y);
-        unpack8(ra[i].z, e.z, o.z);
-        unpack8(ra[i].w, e.w, o.w);
-        *(uint4*)(As + buf * OPER_BYTES + tile_off_bytes(row, 2 * pchunk)) = e;
-        *(uint4*)(As + buf * OPER_BYTES + tile_off_bytes(row, 2 * pchunk + 1)) = o;
-        unpack8(rb[i].x, e.x, o.x);
-        unpack8(rb[i].y, e.y, o.y);
-        unpack8(rb[i].z, e.z, o.z);
-        unpack8(rb[i].w, e.w, o.w);
-        *(uint4*)(Bs + buf * OPER_BYTES + tile_off_bytes(row, 2 * pchunk)) = e;
-        *(uint4*)(Bs + buf * OPER_BYTES + tile_off_bytes(row, 2 * pchunk + 1)) = o;
+        unpack8(rq[i].x, e.x, o.x);
+        unpack8(rq[i].y, e.y, o.y);
+        unpack8(rq[i].z, e.z, o.z);
+        unpack8(rq[i].w, e.w, o.w);
+        *(uint4*)(sb + tile_off_bytes(row, 2 * pchunk)) = e;
+        *(uint4*)(sb + tile_off_bytes(row, 2 * pchunk + 1)) = o;
       }
-      float* sdst = (is_x ? sxs : sws) + buf * (4 * 128);
+      uint32_t* sdst = (uint32_t*)(smem + SCALE_OFF + buf * SCALE_BUF_BYTES);
 #pragma unroll
-      for (int jj = 0; jj < GPS; jj++) sdst[jj * 128 + srow] = f16_bits_to_f32(rs[jj]) * s_mul;
+      for (int jj = 0; jj < GPS; jj++) sdst[jj * ROWS + t] = rs[jj];
     };
+
+    // byte offsets of this lane's scale words (k-slot 0 of the outer-product MFMA lives in
+    // lanes 0..31; lanes 32..63 read a zero word)
+    int soffA[4], soffB[2];
+#pragma unroll
+    for (int i = 0; i < 4; i++) soffA[i] = h ? ZERO_OFF : SCALE_OFF + rowA[i] * 4;
+#pragma unroll
+    for (int j = 0; j < 2; j++) soffB[j] = h ? ZERO_OFF : SCALE_OFF + rowB[j] * 4;
+    const int sstep = h ? 0 : ROWS * 4;       // per group within a stage
+    const int sbufstep = h ? 0 : SCALE_BUF_BYTES;
 
     const int nst = (KL + BKQ - 1) / BKQ;
     gload(0);
@@ -162,106 +152,164 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
     for (int st = 0; st < nst; st++) {
       const int buf = st & 1;
       if (st + 1 < nst) gload(st + 1);
-      const unsigned char* Ab = As + buf * OPER_BYTES;
-      const unsigned char* Bb = Bs + buf * OPER_BYTES;
-      const float* sxb = sxs + buf * (4 * 128);
-      const float* swb = sws + buf * (4 * 128);
+      const unsigned char* sb = smem + buf * STAGE_BYTES;
 #pragma unroll 1
       for (int jj = 0; jj < GPS; jj++) {
-        i32x16 I[2][2];
+        // scale operands of this group: {scale, 0, 0, 0} in lanes 0..31 (k-slot 0), zeros above
+        f16x4 sa[4], sbv[2];
 #pragma unroll
-        for (int i = 0; i < 2; i++)
+        for (int i = 0; i < 4; i++) {
+          const uint32_t wv = *(const uint32_t*)(smem + soffA[i] + buf * sbufstep + jj * sstep);
+          sa[i] = __builtin_bit_cast(f16x4, make_uint2(wv, 0u));
+        }
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+          const uint32_t wv = *(const uint32_t*)(smem + soffB[j] + buf * sbufstep + jj * sstep);
+          sbv[j] = __builtin_bit_cast(f16x4, make_uint2(wv, 0u));
+        }
+        auto lds_op = [&](int row, int kk) {
+          return *(const i32x4*)(sb + row * 128 + (((2 * (jj * MPG + kk) + h) ^ swz) << 4));
+        };
+        auto tile = [&](int i, int j, const i32x4* a, const i32x4* b) {
+          i32x16 I;
+#pragma unroll
+          for (int v = 0; v < 16; v++) I[v] = 0;
+#pragma unroll
+          for (int kk = 0; kk < MPG; kk++) I = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[kk], b[kk], I, 0, 0, 0);
+          f32x16 P;
+#pragma unroll
+          for (int v = 0; v < 16; v++) P[v] = 0.0f;
+          P = __builtin_amdgcn_mfma_f32_32x32x8f16(sa[i], sbv[j], P, 0, 0, 0);
+#pragma unroll
+          for (int v = 0; v < 16; v++) acc[i][j][v] = fmaf((float)I[v], P[v], acc[i][j][v]);
+          __builtin_amdgcn_sched_barrier(0);   // bound the live int32 / scale-product tiles
+        };
+        if constexpr (MPG <= 2) {
+          // token operands of the whole group stay in registers, weight operands stream
+          i32x4 b[2][MPG];
 #pragma unroll
           for (int j = 0; j < 2; j++)
 #pragma unroll
-            for (int v = 0; v < 16; v++) I[i][j][v] = 0;
+            for (int kk = 0; kk < MPG; kk++) b[j][kk] = lds_op(rowB[j], kk);
 #pragma unroll
-        for (int kk = 0; kk < MPG; kk++) {
-          const int chunk = 2 * (jj * MPG + kk) + (l >> 5);
-          i32x4 a[2], b[2];
+          for (int i = 0; i < 4; i++) {
+            i32x4 a[MPG];
 #pragma unroll
-          for (int i = 0; i < 2; i++) {
-            a[i] = *(const i32x4*)(Ab + tile_off_bytes(wm * 64 + i * 32 + (l & 31), chunk));
-            b[i] = *(const i32x4*)(Bb + tile_off_bytes(wn * 64 + i * 32 + (l & 31), chunk));
+            for (int kk = 0; kk < MPG; kk++) a[kk] = lds_op(rowA[i], kk);
+#pragma unroll
+            for (int j = 0; j < 2; j++) tile(i, j, a, b[j]);
           }
+        } else {
+          // 128-channel groups: one token tile at a time to stay inside the register budget
 #pragma unroll
-          for (int i = 0; i < 2; i++)
+          for (int j = 0; j < 2; j++) {
+            i32x4 b[MPG];
 #pragma unroll
-            for (int j = 0; j < 2; j++)
-              I[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], I[i][j], 0, 0, 0);
-        }
-        // dequantize-accumulate: acc += float(256 I) * s_x[m] * (s_w[n] 2^-8)
-        float swl[2];
+            for (int kk = 0; kk < MPG; kk++) b[kk] = lds_op(rowB[j], kk);
 #pragma unroll
-        for (int j = 0; j < 2; j++) swl[j] = swb[jj * 128 + wn * 64 + j * 32 + (l & 31)];
+            for (int i = 0; i < 4; i++) {
+              i32x4 a[MPG];
 #pragma unroll
-        for (int i = 0; i < 2; i++) {
-#pragma unroll
-          for (int q = 0; q < 4; q++) {
-            const float4 s4 = *(const float4*)(sxb + jj * 128 + wm * 64 + i * 32 + 8 * q + 4 * (l >> 5));
-            const float sv[4] = {s4.x, s4.y, s4.z, s4.w};
-#pragma unroll
-            for (int e = 0; e < 4; e++)
-#pragma unroll
-              for (int j = 0; j < 2; j++)
-                acc[i][j][4 * q + e] = fmaf((float)I[i][j][4 * q + e], sv[e] * swl[j], acc[i][j][4 * q + e]);
+              for (int kk = 0; kk < MPG; kk++) a[kk] = lds_op(rowA[i], kk);
+              tile(i, j, a, b);
+            }
           }
         }
       }
       if (st + 1 < nst) sstore(buf ^ 1);
       __syncthreads();
     }
+    // undo the two 16x operand factors (exact power of two)
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+#pragma unroll
+      for (int j = 0; j < 2; j++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) acc[i][j][v] *= 0.00390625f;
   }
 
-  // ---- epilogue: [token][n] fp32 through LDS, 16-byte stores ----------------------
-  float* stage = (float*)smem;
+  // ---- 16-bit branch: acc += W'_h x_h^T, bf16 MFMA, 64 channels per pass ----------
+  if (r > 0) {
+    const int lrow = t >> 3, lchunk = t & 7;   // 8 rows (stride 64) x one 16-B chunk per thread
+    for (int k0 = 0; k0 < r; k0 += 64) {
+      const bool ok = k0 + lchunk * 8 < r;
+      __syncthreads();
 #pragma unroll
-  for (int i = 0; i < 2; i++)
+      for (int i = 0; i < 8; i++) {
+        const int row = lrow + 64 * i;
+        const uint16_t* src = row < TN ? wh + (size_t)min(n0 + row, N - 1) * r
+                                       : xh + (size_t)min(m0 + row - TN, M - 1) * r;
+        const uint4 v = ok ? *(const uint4*)(src + k0 + lchunk * 8) : make_uint4(0, 0, 0, 0);
+        *(uint4*)(smem + tile_off_bytes(row, lchunk)) = v;
+      }
+      __syncthreads();
 #pragma unroll
-    for (int j = 0; j < 2; j++) {
-      const int n = wn * 64 + j * 32 + (l & 31);
+      for (int ks = 0; ks < 4; ks++) {
+        bf16x8 a[4], b[2];
+        const int chunk = 2 * ks + h;
 #pragma unroll
-      for (int v = 0; v < 16; v++) {
-        const int token = wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (l >> 5) + (v & 3);
-        stage[token * STAGE_LD + n] = acc[i][j][v];
+        for (int i = 0; i < 4; i++) a[i] = *(const bf16x8*)(smem + rowA[i] * 128 + ((chunk ^ swz) << 4));
+#pragma unroll
+        for (int j = 0; j < 2; j++) b[j] = *(const bf16x8*)(smem + rowB[j] * 128 + ((chunk ^ swz) << 4));
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+          for (int j = 0; j < 2; j++)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
       }
     }
-  __syncthreads();
-  const bool vec_ok = OUT_F32 ? (N % 4 == 0) : (N % 8 == 0);
-  for (int pass = 0; pass < BM / 16; pass++) {
-    const int row = pass * 16 + (t >> 4), nn = (t & 15) * 8;
-    const int m = m0 + row, n = n0 + nn;
-    if (m >= M || n >= N) continue;
-    const float* src = stage + row * STAGE_LD + nn;
-    float v[8];
-    *(float4*)(v) = *(const float4*)(src);
-    *(float4*)(v + 4) = *(const float4*)(src + 4);
-    if (bias) {
+  }
+
+  // ---- epilogue: 4 consecutive output channels per register quad ------------------
+  const bool vec_ok = (N % 4) == 0;
 #pragma unroll
-      for (int e = 0; e < 8; e++)
-        if (n + e < N) v[e] += bf16_bits_to_f32(bias[n + e]);
-    }
-    if (OUT_F32) {
-      float* dst = (float*)y + (size_t)m * N + n;
-      if (vec_ok && n + 8 <= N) {
-        *(float4*)dst = *(float4*)v;
-        *(float4*)(dst + 4) = *(float4*)(v + 4);
-      } else {
-        for (int e = 0; e < 8 && n + e < N; e++) dst[e] = v[e];
+  for (int j = 0; j < 2; j++) {
+    const int m = m0 + wt * 64 + j * 32 + (l & 31);
+    if (m >= M) continue;
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        const int n = n0 + wn * 128 + i * 32 + 8 * q + 4 * h;
+        if (n >= N) continue;
+        float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+        const bool full = vec_ok && n + 4 <= N;
+        if (bias) {
+          if (full) {
+            const uint2 bb = *(const uint2*)(bias + n);
+            v[0] += bf16_bits_to_f32((uint16_t)(bb.x & 0xFFFF));
+            v[1] += bf16_bits_to_f32((uint16_t)(bb.x >> 16));
+            v[2] += bf16_bits_to_f32((uint16_t)(bb.y & 0xFFFF));
+            v[3] += bf16_bits_to_f32((uint16_t)(bb.y >> 16));
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; e++)
+              if (n + e < N) v[e] += bf16_bits_to_f32(bias[n + e]);
+          }
+        }
+        if (OUT_F32) {
+          float* dst = (float*)y + (size_t)m * N + n;
+          if (full) {
+            *(float4*)dst = make_float4(v[0], v[1], v[2], v[3]);
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; e++)
+              if (n + e < N) dst[e] = v[e];
+          }
+        } else {
+          uint16_t* dst = (uint16_t*)y + (size_t)m * N + n;
+          if (full) {
+            uint2 o;
+            o.x = f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16);
+            o.y = f32_to_bf16_bits(v[2]) | ((uint32_t)f32_to_bf16_bits(v[3]) << 16);
+            *(uint2*)dst = o;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; e++)
+              if (n + e < N) dst[e] = f32_to_bf16_bits(v[e]);
+          }
+        }
       }
-    } else {
-      uint16_t* dst = (uint16_t*)y + (size_t)m * N + n;
-      if (vec_ok && n + 8 <= N) {
-        uint4 o;
-        o.x = f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16);
-        o.y = f32_to_bf16_bits(v[2]) | ((uint32_t)f32_to_bf16_bits(v[3]) << 16);
-        o.z = f32_to_bf16_bits(v[4]) | ((uint32_t)f32_to_bf16_bits(v[5]) << 16);
-        o.w = f32_to_bf16_bits(v[6]) | ((uint32_t)f32_to_bf16_bits(v[7]) << 16);
-        *(uint4*)dst = o;
-      } else {
-        for (int e = 0; e < 8 && n + e < N; e++) dst[e] = f32_to_bf16_bits(v[e]);
-      }
-    }
   }
 }
 
@@ -270,7 +318,7 @@ static int launch_one(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx,
                       const uint16_t* bias, int M, int N, int K, int r, void* y, hipStream_t s) {
   const BlobLayout L = blob_layout(N, K, r, GS);
   const char* bp = (const char*)blob;
-  const int n_mt = (M + BM - 1) / BM, n_nt = (N + BN - 1) / BN;
+  const int n_mt = (M + TM - 1) / TM, n_nt = (N + TN - 1) / TN;
   const long n_blocks = (long)n_mt * n_nt;
   const int per_xcd = (int)((n_blocks + 7) / 8);
   static bool attr_done = false;
