@@ -54,6 +54,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--workload", default="flux", choices=["flux", "pixart", "small"])
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch a plain elementwise copy of known size (256 MiB read + 256 MiB written), "
+                         "the reference the FETCH_SIZE / WRITE_SIZE counters are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (one process, one MI355X, no collectives); "
@@ -98,6 +101,14 @@ def main() -> int:
         layers.append(dict(shape=shp, x=x, Qt=Qt, blob=blob, ws=ws, y=y, Wb=Wb, parts=parts, host=L))
         torch.cuda.synchronize()
         log(f"inputs for {shp.name} ready ({time.time() - t0:.0f} s)")
+
+    if args.calibrate_copy:
+        ca = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+        cb = torch.empty_like(ca)
+        for _ in range(3):
+            torch.mul(ca, 1.0, out=cb)              # one elementwise kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del ca, cb
 
     def step():
         for Ld in layers:
@@ -178,6 +189,15 @@ def main() -> int:
                     "avg_launch_ms": sumB / n_launch, "launches_per_step": n_launch,
                     "algorithmic_flops_per_launch": ops / n_launch, "traffic": None}
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
+    # HBM traffic per launch from the committed rocprofv3 counter summary (FETCH_SIZE + WRITE_SIZE,
+    # scaled by the copy-kernel calibration), if one exists for this kernel and workload
+    tfile = os.path.join(ROOT, "profiles", f"{roofline['kernel']}_{args.workload}_hbm_traffic.txt")
+    if os.path.exists(tfile):
+        for line in open(tfile):
+            if line.startswith("traffic_bytes_per_launch:"):
+                roofline["traffic"] = float(line.split(":")[1])
+        roofline["algorithmic_bytes_per_launch"] = sum(p["_alg"]["A_bytes" if sumA >= sumB else "B_bytes"]
+                                                       for p in per_layer) / n_launch
     other = {"rotate_quantize_kernel": {"sum_ms_per_step": sumA,
                                         "frac_bf16_peak": sum(p["_alg"]["A_flops"] for p in per_layer) / (sumA * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
              "w4a4_gemm_kernel": {"sum_ms_per_step": sumB,
@@ -194,7 +214,7 @@ def main() -> int:
         Ld = layers[min(2, len(layers) - 1)]            # the fc1-shaped layer
         s = Ld["shape"]
         L = Ld["host"]
-        Ms = min(1024, s.M)
+        Ms = s.M
         Wh, qw, sw = O.prepare_weights(L.W, L.Q32, s.r, s.g)          # offline, not timed
         xs = I.bf16_bits_to_f32(L.x_bits[:Ms])
         Qb = I.bf16_bits_to_f32(L.Q_bits)
@@ -208,8 +228,9 @@ def main() -> int:
         cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
         cpu = {"value": 2.0 * Ms * s.N * s.K / dt / 1e12, "unit": "TOPS", "cores": cores, "kind": "oracle",
                "seconds": round(dt, 2),
-               "sample": f"online part of the NumPy oracle (rotate, quantize, combine) on the first {Ms} tokens "
-                         f"of {s.name} (K={s.K}, N={s.N}); effective ops 2*{Ms}*N*K"}
+               "sample": f"online part of the NumPy oracle (rotate, quantize, combine; float64 BLAS for the sums) on "
+                         f"{Ms} tokens of {s.name} (K={s.K}, N={s.N}), one of the four layers of a step; "
+                         f"effective ops 2*{Ms}*N*K; the offline weight preparation is not timed"}
         log(f"oracle on {Ms} tokens of {s.name}: {dt:.1f} s on {cores} cores")
 
     out = {

@@ -3,8 +3,9 @@
 //
 // Orientation.  D[n][token]: output channels on the MFMA row axis, tokens on the column
 // axis, so a lane owns one token and 4 consecutive output channels per register quad
-// (one 8-byte bf16 store).  Workgroup tile 256 n x 256 tokens, 8 waves as 2 (n) x 4
-// (tokens), each 128 n x 64 tokens.
+// (one 8-byte bf16 store).  Workgroup tile 128 n x 128 tokens, 4 waves as 2 (n) x 2
+// (tokens), each 64 n x 64 tokens = 2 x 2 MFMA tiles; two workgroups share a CU so that
+// one's barrier / staging phase overlaps the other's arithmetic.
 //
 // Integer part.  INT4 codes are unpacked once per workgroup on their way into LDS: a
 // nibble is moved to the high half of a byte, so the i8 MFMA operand holds 16 q and the
@@ -18,20 +19,26 @@
 // leaves the vector ALU one convert and one fma per accumulator and group:
 // acc += float(256 I) * P.  The common factor 2^-8 is applied once at the end (exact),
 // before the 16-bit branch is accumulated on top by bf16 MFMAs.
+//
+// Schedule.  The vector ALU is the binding unit (2 ops per accumulator and group against
+// 64 cycles of i8 MFMA per tile and group), so the main loop is software-pipelined by
+// hand: the MFMAs of tile s+1 are issued before the convert/fma sweep of tile s, and the
+// LDS operand reads of the next group are issued one sweep ahead.
 #include "dirotq_internal.h"
 
 namespace dirotq {
 
-constexpr int TN = 256;         // output channels per workgroup tile
-constexpr int TM = 256;         // tokens per workgroup tile
+constexpr int TN = 128;         // output channels per workgroup tile
+constexpr int TM = 128;         // tokens per workgroup tile
 constexpr int BKQ = 128;        // 4-bit channels per LDS stage (one 128-byte i8 row)
-constexpr int NTHREADS = 512;   // 8 waves as 2 (n) x 4 (tokens), 128 n x 64 tokens each
+constexpr int NTHREADS = 256;   // 4 waves as 2 (n) x 2 (tokens), 64 n x 64 tokens each
 constexpr int ROWS = TN + TM;
-constexpr int STAGE_BYTES = ROWS * 128;              // i8 [512 rows][128 B] (= bf16 [512][64])
-constexpr int SCALE_OFF = 2 * STAGE_BYTES;           // u32 [2 bufs][4 groups][512 rows]: fp16 scale, zero-extended
-constexpr int SCALE_BUF_BYTES = 4 * ROWS * 4;
-constexpr int ZERO_OFF = SCALE_OFF + 2 * SCALE_BUF_BYTES;
-constexpr int SMEM_BYTES = ZERO_OFF + 256;
+constexpr int STAGE_BYTES = ROWS * 128;              // i8 [256 rows][128 B] (= bf16 [256][64])
+constexpr int SCALE_OFF = 2 * STAGE_BYTES;           // u64 [2 bufs][4 groups][256 rows]: {fp16 scale, 0, 0, 0}
+// per buffer: (groups per stage) x ROWS x 8 bytes, then 8 zero bytes read by lanes 32..63
+constexpr int scale_buf_bytes(int gs) { return (BKQ / gs) * ROWS * 8; }
+constexpr int zero_off(int gs) { return SCALE_OFF + 2 * scale_buf_bytes(gs); }
+constexpr int smem_bytes(int gs) { return zero_off(gs) + 256; }
 
 // [rows][128 B] tiles, 16-B chunk c of row r stored at slot c ^ ((r >> 1) & 7): LDS has
 // 64 banks and serves 16-byte accesses 16 lanes per cycle, so 16 consecutive rows must
@@ -70,21 +77,22 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
   const int G = KL / GS;
   constexpr int GPS = BKQ / GS;    // groups per stage
   constexpr int MPG = GS / 32;     // i8 MFMAs (k = 32) per group
+  constexpr int SCALE_BUF_BYTES = scale_buf_bytes(GS), ZERO_OFF = zero_off(GS);
 
-  if (t < 64) ((uint32_t*)(smem + ZERO_OFF))[t] = 0u;
+  if (t < 64) ((uint32_t*)(smem + ZERO_OFF))[t] = 0u;   // read as the zero operand half
 
-  f32x16 acc[4][2];
+  f32x16 acc[2][2];
 #pragma unroll
-  for (int i = 0; i < 4; i++)
+  for (int i = 0; i < 2; i++)
 #pragma unroll
     for (int j = 0; j < 2; j++)
 #pragma unroll
       for (int v = 0; v < 16; v++) acc[i][j][v] = 0.0f;
 
-  // operand rows of this lane: A = weights (rows 0..255 of a stage), B = tokens (256..511)
-  int rowA[4], rowB[2];
+  // operand rows of this lane: A = weights (rows 0..127 of a stage), B = tokens (128..255)
+  int rowA[2], rowB[2];
 #pragma unroll
-  for (int i = 0; i < 4; i++) rowA[i] = wn * 128 + i * 32 + (l & 31);
+  for (int i = 0; i < 2; i++) rowA[i] = wn * 64 + i * 32 + (l & 31);
 #pragma unroll
   for (int j = 0; j < 2; j++) rowB[j] = TN + wt * 64 + j * 32 + (l & 31);
   const int swz = ((l & 31) >> 1) & 7;                 // tile bases are multiples of 32 rows
@@ -92,16 +100,17 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
   // ---- 4-bit branch ---------------------------------------------------------------
   if (KL > 0) {
     const size_t ldq = (size_t)KL / 2;        // packed bytes per row
-    const int prow = t >> 2, pchunk = t & 3;  // 4 rows (stride 128) x one 16-B packed chunk per thread
+    const int prow = t >> 2, pchunk = t & 3;  // 4 rows (stride 64) x one 16-B packed chunk per thread
     const uint8_t* gq[4];
 #pragma unroll
     for (int i = 0; i < 4; i++) {
-      const int row = prow + 128 * i;
+      const int row = prow + 64 * i;
       gq[i] = (row < TN ? wq + (size_t)min(n0 + row, N - 1) * ldq : xl + (size_t)min(m0 + row - TN, M - 1) * ldq) +
               pchunk * 16;
     }
     // scale staging: thread t owns row t of the stage (weights then tokens)
-    const uint16_t* gs = t < TN ? sw + min(n0 + t, N - 1) : sx + min(m0 + t - TN, M - 1);
+    const int ts = t;
+    const uint16_t* gs = ts < TN ? sw + min(n0 + ts, N - 1) : sx + min(m0 + ts - TN, M - 1);
     const size_t s_ld = t < TN ? (size_t)N : (size_t)M;
 
     uint4 rq[4];
@@ -117,11 +126,11 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
         rs[jj] = j < G ? gs[(size_t)j * s_ld] : (uint16_t)0;
       }
     };
-    auto sstore = [&](int buf) {
+    // unpack one staged chunk (or the scales) into the LDS stage `buf`
+    auto sstore_piece = [&](int buf, int i) {
       unsigned char* sb = smem + buf * STAGE_BYTES;
-#pragma unroll
-      for (int i = 0; i < 4; i++) {
-        const int row = prow + 128 * i;
+      if (i < 4) {
+        const int row = prow + 64 * i;
         uint4 e, o;
         unpack8(rq[i].x, e.x, o.x);
         unpack8(rq[i].y, e.y, o.y);
@@ -129,99 +138,120 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
         unpack8(rq[i].w, e.w, o.w);
         *(uint4*)(sb + tile_off_bytes(row, 2 * pchunk)) = e;
         *(uint4*)(sb + tile_off_bytes(row, 2 * pchunk + 1)) = o;
-      }
-      uint32_t* sdst = (uint32_t*)(smem + SCALE_OFF + buf * SCALE_BUF_BYTES);
+      } else {
+        uint2* sdst = (uint2*)(smem + SCALE_OFF + buf * SCALE_BUF_BYTES);
 #pragma unroll
-      for (int jj = 0; jj < GPS; jj++) sdst[jj * ROWS + t] = rs[jj];
+        for (int jj = 0; jj < GPS; jj++)
+          sdst[jj * ROWS + t] = make_uint2(rs[jj], 0u);
+      }
     };
 
-    // byte offsets of this lane's scale words (k-slot 0 of the outer-product MFMA lives in
-    // lanes 0..31; lanes 32..63 read a zero word)
-    int soffA[4], soffB[2];
+    // per-lane LDS addresses: operand chunk k (0..3) of each tile row, and the scale words
+    // (k-slot 0 of the outer-product MFMA lives in lanes 0..31; lanes 32..63 read zeros)
+    int adA[2][4], adB[2][4];
 #pragma unroll
-    for (int i = 0; i < 4; i++) soffA[i] = h ? ZERO_OFF : SCALE_OFF + rowA[i] * 4;
+    for (int k = 0; k < 4; k++) {
+      const int off = ((2 * k + h) ^ swz) << 4;
 #pragma unroll
-    for (int j = 0; j < 2; j++) soffB[j] = h ? ZERO_OFF : SCALE_OFF + rowB[j] * 4;
-    const int sstep = h ? 0 : ROWS * 4;       // per group within a stage
+      for (int i = 0; i < 2; i++) adA[i][k] = rowA[i] * 128 + off;
+#pragma unroll
+      for (int j = 0; j < 2; j++) adB[j][k] = rowB[j] * 128 + off;
+    }
+    int soffA[2], soffB[2];
+#pragma unroll
+    for (int i = 0; i < 2; i++) soffA[i] = h ? ZERO_OFF : SCALE_OFF + rowA[i] * 8;
+#pragma unroll
+    for (int j = 0; j < 2; j++) soffB[j] = h ? ZERO_OFF : SCALE_OFF + rowB[j] * 8;
+    const int sstep = h ? 0 : ROWS * 8;       // per group within a stage
     const int sbufstep = h ? 0 : SCALE_BUF_BYTES;
 
     const int nst = (KL + BKQ - 1) / BKQ;
     gload(0);
-    sstore(0);
+#pragma unroll
+    for (int i = 0; i < 5; i++) sstore_piece(0, i);
     __syncthreads();
     for (int st = 0; st < nst; st++) {
       const int buf = st & 1;
-      if (st + 1 < nst) gload(st + 1);
+      const bool more_st = st + 1 < nst;
+      if (more_st) gload(st + 1);
       const unsigned char* sb = smem + buf * STAGE_BYTES;
-#pragma unroll 1
+      const unsigned char* ssb = smem + buf * sbufstep;
+      // operands of one group: i8 codes of 2 weight tiles and 2 token tiles, and their scales
+      i32x4 a[2][MPG], b[2][MPG];
+      f16x4 sa[2], sbv[2];
+      auto load_ops = [&](int jj) {
+#pragma unroll
+        for (int kk = 0; kk < MPG; kk++) {
+#pragma unroll
+          for (int i = 0; i < 2; i++) a[i][kk] = *(const i32x4*)(sb + adA[i][jj * MPG + kk]);
+#pragma unroll
+          for (int j = 0; j < 2; j++) b[j][kk] = *(const i32x4*)(sb + adB[j][jj * MPG + kk]);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; i++) sa[i] = *(const f16x4*)(ssb + soffA[i] + jj * sstep);
+#pragma unroll
+        for (int j = 0; j < 2; j++) sbv[j] = *(const f16x4*)(ssb + soffB[j] + jj * sstep);
+      };
+      i32x16 I[2];
+      f32x16 P[2];
+      auto issue = [&](int i, int j, int slot) {     // 256 I and the scale product of tile (i, j)
+        i32x16 z;
+#pragma unroll
+        for (int v = 0; v < 16; v++) z[v] = 0;
+#pragma unroll
+        for (int kk = 0; kk < MPG; kk++) z = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i][kk], b[j][kk], z, 0, 0, 0);
+        I[slot] = z;
+        f32x16 p;
+#pragma unroll
+        for (int v = 0; v < 16; v++) p[v] = 0.0f;
+        P[slot] = __builtin_amdgcn_mfma_f32_32x32x8f16(sa[i], sbv[j], p, 0, 0, 0);
+      };
+      auto sweep = [&](int i, int j, int slot) {     // acc += float(256 I) * P for tile (i, j)
+#pragma unroll
+        for (int v = 0; v < 16; v++) acc[i][j][v] = fmaf((float)I[slot][v], P[slot][v], acc[i][j][v]);
+        asm volatile("" : "+v"(acc[i][j]));            // pin the sweep here (keeps I/P live ranges short)
+      };
+      // the next stage's unpack work is spread over the last four tile sweeps of this stage
+      constexpr int NSTEP = GPS * 4;
+      auto stage_piece = [&](int step) {
+        if (more_st && step >= NSTEP - 4) {
+          sstore_piece(buf ^ 1, step - (NSTEP - 4));
+          if (step == NSTEP - 1) sstore_piece(buf ^ 1, 4);   // scales
+        }
+      };
+      load_ops(0);
+      issue(0, 0, 0);
+#pragma unroll
       for (int jj = 0; jj < GPS; jj++) {
-        // scale operands of this group: {scale, 0, 0, 0} in lanes 0..31 (k-slot 0), zeros above
-        f16x4 sa[4], sbv[2];
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-          const uint32_t wv = *(const uint32_t*)(smem + soffA[i] + buf * sbufstep + jj * sstep);
-          sa[i] = __builtin_bit_cast(f16x4, make_uint2(wv, 0u));
-        }
-#pragma unroll
-        for (int j = 0; j < 2; j++) {
-          const uint32_t wv = *(const uint32_t*)(smem + soffB[j] + buf * sbufstep + jj * sstep);
-          sbv[j] = __builtin_bit_cast(f16x4, make_uint2(wv, 0u));
-        }
-        auto lds_op = [&](int row, int kk) {
-          return *(const i32x4*)(sb + row * 128 + (((2 * (jj * MPG + kk) + h) ^ swz) << 4));
-        };
-        auto tile = [&](int i, int j, const i32x4* a, const i32x4* b) {
-          i32x16 I;
-#pragma unroll
-          for (int v = 0; v < 16; v++) I[v] = 0;
-#pragma unroll
-          for (int kk = 0; kk < MPG; kk++) I = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[kk], b[kk], I, 0, 0, 0);
-          f32x16 P;
-#pragma unroll
-          for (int v = 0; v < 16; v++) P[v] = 0.0f;
-          P = __builtin_amdgcn_mfma_f32_32x32x8f16(sa[i], sbv[j], P, 0, 0, 0);
-#pragma unroll
-          for (int v = 0; v < 16; v++) acc[i][j][v] = fmaf((float)I[v], P[v], acc[i][j][v]);
-          __builtin_amdgcn_sched_barrier(0);   // bound the live int32 / scale-product tiles
-        };
-        if constexpr (MPG <= 2) {
-          // token operands of the whole group stay in registers, weight operands stream
-          i32x4 b[2][MPG];
-#pragma unroll
-          for (int j = 0; j < 2; j++)
-#pragma unroll
-            for (int kk = 0; kk < MPG; kk++) b[j][kk] = lds_op(rowB[j], kk);
-#pragma unroll
-          for (int i = 0; i < 4; i++) {
-            i32x4 a[MPG];
-#pragma unroll
-            for (int kk = 0; kk < MPG; kk++) a[kk] = lds_op(rowA[i], kk);
-#pragma unroll
-            for (int j = 0; j < 2; j++) tile(i, j, a, b[j]);
-          }
-        } else {
-          // 128-channel groups: one token tile at a time to stay inside the register budget
-#pragma unroll
-          for (int j = 0; j < 2; j++) {
-            i32x4 b[MPG];
-#pragma unroll
-            for (int kk = 0; kk < MPG; kk++) b[kk] = lds_op(rowB[j], kk);
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-              i32x4 a[MPG];
-#pragma unroll
-              for (int kk = 0; kk < MPG; kk++) a[kk] = lds_op(rowA[i], kk);
-              tile(i, j, a, b);
-            }
-          }
-        }
+        const bool more = jj + 1 < GPS;              // compile-time after unrolling
+        issue(0, 1, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        sweep(0, 0, 0);
+        stage_piece(jj * 4 + 0);
+        __builtin_amdgcn_sched_barrier(0);
+        issue(1, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        sweep(0, 1, 1);
+        stage_piece(jj * 4 + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        issue(1, 1, 1);
+        asm volatile("" ::: "memory");               // keep the next group's LDS reads below this point
+        if (more) load_ops(jj + 1);                  // every MFMA of this group is issued
+        __builtin_amdgcn_sched_barrier(0);
+        sweep(1, 0, 0);
+        stage_piece(jj * 4 + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) issue(0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        sweep(1, 1, 1);
+        stage_piece(jj * 4 + 3);
+        __builtin_amdgcn_sched_barrier(0);
       }
-      if (st + 1 < nst) sstore(buf ^ 1);
       __syncthreads();
     }
     // undo the two 16x operand factors (exact power of two)
 #pragma unroll
-    for (int i = 0; i < 4; i++)
+    for (int i = 0; i < 2; i++)
 #pragma unroll
       for (int j = 0; j < 2; j++)
 #pragma unroll
@@ -230,13 +260,13 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
 
   // ---- 16-bit branch: acc += W'_h x_h^T, bf16 MFMA, 64 channels per pass ----------
   if (r > 0) {
-    const int lrow = t >> 3, lchunk = t & 7;   // 8 rows (stride 64) x one 16-B chunk per thread
+    const int lrow = t >> 3, lchunk = t & 7;   // 8 rows (stride 32) x one 16-B chunk per thread
     for (int k0 = 0; k0 < r; k0 += 64) {
       const bool ok = k0 + lchunk * 8 < r;
       __syncthreads();
 #pragma unroll
       for (int i = 0; i < 8; i++) {
-        const int row = lrow + 64 * i;
+        const int row = lrow + 32 * i;
         const uint16_t* src = row < TN ? wh + (size_t)min(n0 + row, N - 1) * r
                                        : xh + (size_t)min(m0 + row - TN, M - 1) * r;
         const uint4 v = ok ? *(const uint4*)(src + k0 + lchunk * 8) : make_uint4(0, 0, 0, 0);
@@ -245,14 +275,14 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
       __syncthreads();
 #pragma unroll
       for (int ks = 0; ks < 4; ks++) {
-        bf16x8 a[4], b[2];
+        bf16x8 a[2], b[2];
         const int chunk = 2 * ks + h;
 #pragma unroll
-        for (int i = 0; i < 4; i++) a[i] = *(const bf16x8*)(smem + rowA[i] * 128 + ((chunk ^ swz) << 4));
+        for (int i = 0; i < 2; i++) a[i] = *(const bf16x8*)(smem + rowA[i] * 128 + ((chunk ^ swz) << 4));
 #pragma unroll
         for (int j = 0; j < 2; j++) b[j] = *(const bf16x8*)(smem + rowB[j] * 128 + ((chunk ^ swz) << 4));
 #pragma unroll
-        for (int i = 0; i < 4; i++)
+        for (int i = 0; i < 2; i++)
 #pragma unroll
           for (int j = 0; j < 2; j++)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
@@ -267,10 +297,10 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
     const int m = m0 + wt * 64 + j * 32 + (l & 31);
     if (m >= M) continue;
 #pragma unroll
-    for (int i = 0; i < 4; i++)
+    for (int i = 0; i < 2; i++)
 #pragma unroll
       for (int q = 0; q < 4; q++) {
-        const int n = n0 + wn * 128 + i * 32 + 8 * q + 4 * h;
+        const int n = n0 + wn * 64 + i * 32 + 8 * q + 4 * h;
         if (n >= N) continue;
         float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
         const bool full = vec_ok && n + 4 <= N;
@@ -324,11 +354,11 @@ static int launch_one(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx,
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void*)w4a4_gemm_kernel<GS, OUT_F32>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes(GS));
     if (e != hipSuccess) return hip_failed(e);
     attr_done = true;
   }
-  hipLaunchKernelGGL((w4a4_gemm_kernel<GS, OUT_F32>), dim3(per_xcd * 8), dim3(NTHREADS), SMEM_BYTES, s, xh,
+  hipLaunchKernelGGL((w4a4_gemm_kernel<GS, OUT_F32>), dim3(per_xcd * 8), dim3(NTHREADS), smem_bytes(GS), s, xh,
                      xl, sx, (const uint16_t*)(bp + L.off_wh), (const uint8_t*)(bp + L.off_codes),
                      (const uint16_t*)(bp + L.off_sw), bias, M, N, K, r, y, n_mt, n_nt, per_xcd);
   hipError_t e = hipGetLastError();
