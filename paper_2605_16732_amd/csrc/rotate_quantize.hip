@@ -21,9 +21,6 @@
 namespace dirotq {
 
 typedef __attribute__((address_space(3))) void lds_void;
-#ifndef DIROTQ_RQ_AUX
-#define DIROTQ_RQ_AUX 0
-#endif
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
@@ -51,7 +48,7 @@ struct RQ {
   __device__ static __forceinline__ int swz(int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
 };
 
-template <int WGC, int WGT, int BK, int NBUF>
+template <int WGC, int WGT, int BK, int NBUF, bool DMA, bool PF>
 __global__ __launch_bounds__(WGC* WGT * 64, 2) void rotate_quantize_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ Qt, int M, int K, int r, int g,
     uint16_t* __restrict__ xh, uint8_t* __restrict__ xl, uint16_t* __restrict__ sx, int r_pad, int Kv, int n_ct,
@@ -84,37 +81,32 @@ __global__ __launch_bounds__(WGC* WGT * 64, 2) void rotate_quantize_kernel(
     const int logical_chunk = phys ^ C::swz(row);
     const uint16_t* base;
     if (row < C::TC) {
-#ifdef DIROTQ_EXP_SAMETILE
-      const int v = row;
-#else
       const int v = ct * C::TC + row;                       // virtual channel
-#endif
       int ch = v < r_pad ? min(v, r - 1) : min(r + (v - r_pad), K - 1);
       ch = max(ch, 0);
       base = Qt + (size_t)ch * K;
     } else {
-#ifdef DIROTQ_EXP_SAMETILE
-      base = x + (size_t)min(row - C::TC, M - 1) * K;
-#else
       base = x + (size_t)min(m0 + row - C::TC, M - 1) * K;
-#endif
     }
     gsrc[i] = base + logical_chunk * 8;
   }
-  auto issue_part = [&](int kt, int buf, int part, int nparts) {
-#pragma unroll
-    for (int i = 0; i < C::IPW; i++)
-      if (i * nparts / C::IPW == part)
-        __builtin_amdgcn_global_load_lds((const void*)(gsrc[i] + kt * BK),
-                                         (lds_void*)(smem + buf * C::STAGE_BYTES + (w * C::IPW + i) * 1024), 16,
-                                         0, DIROTQ_RQ_AUX);
-  };
-  auto issue = [&](int kt, int buf) {
+  auto issue = [&](int kt, int buf) {      // HBM -> LDS, one stage, asynchronous
 #pragma unroll
     for (int i = 0; i < C::IPW; i++)
       __builtin_amdgcn_global_load_lds((const void*)(gsrc[i] + kt * BK),
                                        (lds_void*)(smem + buf * C::STAGE_BYTES + (w * C::IPW + i) * 1024), 16, 0,
-                                       DIROTQ_RQ_AUX);
+                                       0);
+  };
+  // alternative staging through registers (same LDS image)
+  uint4 stg[DMA ? 1 : C::IPW];
+  auto gload = [&](int kt) {
+#pragma unroll
+    for (int i = 0; i < C::IPW; i++) stg[DMA ? 0 : i] = *(const uint4*)(gsrc[i] + kt * BK);
+  };
+  auto sstore = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < C::IPW; i++)
+      *(uint4*)(smem + buf * C::STAGE_BYTES + (w * C::IPW + i) * 1024 + l * 16) = stg[DMA ? 0 : i];
   };
 
   f32x16 acc[4][2];
@@ -134,64 +126,69 @@ __global__ __launch_bounds__(WGC* WGT * 64, 2) void rotate_quantize_kernel(
   const int swzA = C::swz(l & 31), swzB = C::swz(l & 31);   // tile bases are multiples of 32 rows
 
   const int nk = K / BK;                                    // the launcher guarantees K % BK == 0
+  auto compute = [&](const unsigned char* sb) {
+    if constexpr (PF) {
+      // operands of k-step ks+1 are fetched from LDS while the MFMAs of k-step ks run
+      bf16x8 a[2][4], b[2][2];
+      auto lds_fetch = [&](int ks, int slot) {
+        const int chunk = 2 * ks + (l >> 5);
 #pragma unroll
-  for (int s = 0; s < NBUF - 1; s++)
-    if (s < nk) issue(s, s);
-
-  for (int kt = 0; kt < nk; kt++) {
-    const int rem = nk - 1 - kt;                            // stages issued after stage kt
-    if (NBUF >= 4 && rem >= 2) wait_vmcnt<2 * C::IPW>();
-    else if (NBUF >= 3 && rem >= 1) wait_vmcnt<1 * C::IPW>();
-    else wait_vmcnt<0>();
-#ifndef DIROTQ_EXP_NOBAR
+        for (int i = 0; i < 4; i++) a[slot][i] = *(const bf16x8*)(sb + offA[i] + ((chunk ^ swzA) << 4));
+#pragma unroll
+        for (int j = 0; j < 2; j++) b[slot][j] = *(const bf16x8*)(sb + offB[j] + ((chunk ^ swzB) << 4));
+      };
+      lds_fetch(0, 0);
+#pragma unroll
+      for (int ks = 0; ks < BK / 16; ks++) {
+        if (ks + 1 < BK / 16) lds_fetch(ks + 1, (ks + 1) & 1);
+        __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads ahead of this k-step's MFMAs
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+          for (int j = 0; j < 2; j++)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][i], b[ks & 1][j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < BK / 16; ks++) {
+        const int chunk = 2 * ks + (l >> 5);
+        bf16x8 a[4], b[2];
+#pragma unroll
+        for (int i = 0; i < 4; i++) a[i] = *(const bf16x8*)(sb + offA[i] + ((chunk ^ swzA) << 4));
+#pragma unroll
+        for (int j = 0; j < 2; j++) b[j] = *(const bf16x8*)(sb + offB[j] + ((chunk ^ swzB) << 4));
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+          for (int j = 0; j < 2; j++)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+      }
+    }
+  };
+  if constexpr (DMA) {
+#pragma unroll
+    for (int s = 0; s < NBUF - 1; s++)
+      if (s < nk) issue(s, s);
+    for (int kt = 0; kt < nk; kt++) {
+      const int rem = nk - 1 - kt;                          // stages issued after stage kt
+      if (NBUF >= 4 && rem >= 2) wait_vmcnt<2 * C::IPW>();
+      else if (NBUF >= 3 && rem >= 1) wait_vmcnt<1 * C::IPW>();
+      else wait_vmcnt<0>();
+      __syncthreads();
+      if (kt + NBUF - 1 < nk) issue(kt + NBUF - 1, (kt + NBUF - 1) % NBUF);
+      compute(smem + (kt % NBUF) * C::STAGE_BYTES);
+    }
+  } else {
+    gload(0);
+    sstore(0);
     __syncthreads();
-#endif
-    const bool more = kt + NBUF - 1 < nk;
-#if !defined(DIROTQ_EXP_NOLOAD) && !defined(DIROTQ_RQ_SPREAD)
-    if (more) issue(kt + NBUF - 1, (kt + NBUF - 1) % NBUF);
-#endif
-    const unsigned char* sb = smem + (kt % NBUF) * C::STAGE_BYTES;
-#ifdef DIROTQ_RQ_PREFETCH
-    // operands of k-step ks+1 are fetched from LDS while the MFMAs of k-step ks run
-    bf16x8 a[2][4], b[2][2];
-    auto lds_fetch = [&](int ks, int slot) {
-      const int chunk = 2 * ks + (l >> 5);
-#pragma unroll
-      for (int i = 0; i < 4; i++) a[slot][i] = *(const bf16x8*)(sb + offA[i] + ((chunk ^ swzA) << 4));
-#pragma unroll
-      for (int j = 0; j < 2; j++) b[slot][j] = *(const bf16x8*)(sb + offB[j] + ((chunk ^ swzB) << 4));
-    };
-    lds_fetch(0, 0);
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ks++) {
-      if (ks + 1 < BK / 16) lds_fetch(ks + 1, (ks + 1) & 1);
-      __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads ahead of this k-step's MFMAs
-#pragma unroll
-      for (int i = 0; i < 4; i++)
-#pragma unroll
-        for (int j = 0; j < 2; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][i], b[ks & 1][j], acc[i][j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
+    for (int kt = 0; kt < nk; kt++) {
+      if (kt + 1 < nk) gload(kt + 1);
+      compute(smem + (kt & 1) * C::STAGE_BYTES);
+      if (kt + 1 < nk) sstore((kt + 1) & 1);
+      __syncthreads();
     }
-#else
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ks++) {
-      const int chunk = 2 * ks + (l >> 5);
-      bf16x8 a[4], b[2];
-#pragma unroll
-      for (int i = 0; i < 4; i++) a[i] = *(const bf16x8*)(sb + offA[i] + ((chunk ^ swzA) << 4));
-#pragma unroll
-      for (int j = 0; j < 2; j++) b[j] = *(const bf16x8*)(sb + offB[j] + ((chunk ^ swzB) << 4));
-#ifdef DIROTQ_RQ_SPREAD
-      if (more) issue_part(kt + NBUF - 1, (kt + NBUF - 1) % NBUF, ks, BK / 16);
-#endif
-#pragma unroll
-      for (int i = 0; i < 4; i++)
-#pragma unroll
-        for (int j = 0; j < 2; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-    }
-#endif
   }
 
   // ---- epilogue, in registers ------------------------------------------------------
@@ -269,7 +266,7 @@ __global__ __launch_bounds__(WGC* WGT * 64, 2) void rotate_quantize_kernel(
   }
 }
 
-template <int WGC, int WGT, int BK, int NBUF>
+template <int WGC, int WGT, int BK, int NBUF, bool DMA = true, bool PF = false>
 static int launch_cfg(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g, uint16_t* xh,
                       uint8_t* xl, uint16_t* sx, hipStream_t s) {
   using C = RQ<WGC, WGT, BK, NBUF>;
@@ -281,12 +278,12 @@ static int launch_cfg(const uint16_t* x, const uint16_t* Qt, int M, int K, int r
   const int per_xcd = (int)((n_blocks + 7) / 8);
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)rotate_quantize_kernel<WGC, WGT, BK, NBUF>,
+    hipError_t e = hipFuncSetAttribute((const void*)rotate_quantize_kernel<WGC, WGT, BK, NBUF, DMA, PF>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
     if (e != hipSuccess) return hip_failed(e);
     attr_done = true;
   }
-  hipLaunchKernelGGL((rotate_quantize_kernel<WGC, WGT, BK, NBUF>), dim3(per_xcd * 8), dim3(C::NT), C::SMEM, s, x,
+  hipLaunchKernelGGL((rotate_quantize_kernel<WGC, WGT, BK, NBUF, DMA, PF>), dim3(per_xcd * 8), dim3(C::NT), C::SMEM, s, x,
                      Qt, M, K, r, g, xh, xl, sx, r_pad, Kv, n_ct, n_tt, per_xcd);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? DIROTQ_OK : hip_failed(e);
@@ -305,7 +302,7 @@ int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, 
   return launch_cfg<DIROTQ_RQ_FORCE>(x, Qt, M, K, r, g, xh, xl, sx, s);
 #endif
   if (K % 64 != 0) return launch_cfg<1, 2, 32, 4>(x, Qt, M, K, r, g, xh, xl, sx, s);
-  if (big_tiles >= 200) return launch_cfg<2, 4, 64, 2>(x, Qt, M, K, r, g, xh, xl, sx, s);
+  if (big_tiles >= 200) return launch_cfg<2, 4, 64, 2, true, true>(x, Qt, M, K, r, g, xh, xl, sx, s);
   if (mid_tiles >= 100) return launch_cfg<2, 2, 64, 2>(x, Qt, M, K, r, g, xh, xl, sx, s);
   return launch_cfg<1, 2, 64, 2>(x, Qt, M, K, r, g, xh, xl, sx, s);
 }

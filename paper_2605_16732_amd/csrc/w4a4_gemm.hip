@@ -101,29 +101,38 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
   if (KL > 0) {
     const size_t ldq = (size_t)KL / 2;        // packed bytes per row
     const int prow = t >> 2, pchunk = t & 3;  // 4 rows (stride 64) x one 16-B packed chunk per thread
+    const int pc16 = min(pchunk * 16, (int)ldq - 16);   // this thread's chunk, kept inside the row
     const uint8_t* gq[4];
 #pragma unroll
     for (int i = 0; i < 4; i++) {
       const int row = prow + 64 * i;
       gq[i] = (row < TN ? wq + (size_t)min(n0 + row, N - 1) * ldq : xl + (size_t)min(m0 + row - TN, M - 1) * ldq) +
-              pchunk * 16;
+              pc16;
     }
     // scale staging: thread t owns row t of the stage (weights then tokens)
     const int ts = t;
     const uint16_t* gs = ts < TN ? sw + min(n0 + ts, N - 1) : sx + min(m0 + ts - TN, M - 1);
     const size_t s_ld = t < TN ? (size_t)N : (size_t)M;
 
+    // Staging registers: chunk i (i < 4) / the scales (i == 4) of one stage.  Each piece is
+    // reloaded for stage s+2 right after it has been unpacked into LDS for stage s+1, so a
+    // global load has a whole stage of arithmetic to complete.
     uint4 rq[4];
     uint16_t rs[GPS];
-    auto gload = [&](int st) {
-      const bool ok = st * BKQ + pchunk * 32 < KL;
+    // Loads are unconditional (straight-line code keeps the outstanding-load count exact):
+    // a chunk past the end of the row is re-read from the row's last chunk and belongs to a
+    // group >= G, whose scale is forced to zero, so it contributes exactly nothing.
+    const int last_chunk = (int)ldq - 16 - pc16;            // largest in-row offset for this thread (>= 0)
+    auto gload_piece = [&](int st, int i) {
+      if (i < 4) {
+        rq[i] = *(const uint4*)(gq[i] + min(st * (BKQ / 2), last_chunk));
+      } else {
 #pragma unroll
-      for (int i = 0; i < 4; i++)
-        rq[i] = ok ? *(const uint4*)(gq[i] + (size_t)st * (BKQ / 2)) : make_uint4(0, 0, 0, 0);
-#pragma unroll
-      for (int jj = 0; jj < GPS; jj++) {
-        const int j = st * GPS + jj;
-        rs[jj] = j < G ? gs[(size_t)j * s_ld] : (uint16_t)0;
+        for (int jj = 0; jj < GPS; jj++) {
+          const int j = st * GPS + jj;
+          const uint16_t v = gs[(size_t)min(j, G - 1) * s_ld];
+          rs[jj] = (uint16_t)(v & (j < G ? 0xFFFFu : 0u));
+        }
       }
     };
     // unpack one staged chunk (or the scales) into the LDS stage `buf`
@@ -166,14 +175,17 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
     const int sbufstep = h ? 0 : SCALE_BUF_BYTES;
 
     const int nst = (KL + BKQ - 1) / BKQ;
-    gload(0);
 #pragma unroll
-    for (int i = 0; i < 5; i++) sstore_piece(0, i);
+    for (int i = 0; i < 5; i++) gload_piece(0, i);
+#pragma unroll
+    for (int i = 0; i < 5; i++) {
+      sstore_piece(0, i);
+      gload_piece(min(1, nst - 1), i);
+    }
     __syncthreads();
     for (int st = 0; st < nst; st++) {
       const int buf = st & 1;
-      const bool more_st = st + 1 < nst;
-      if (more_st) gload(st + 1);
+      const int st2 = min(st + 2, nst - 1);     // past the end: harmless re-load, never used
       const unsigned char* sb = smem + buf * STAGE_BYTES;
       const unsigned char* ssb = smem + buf * sbufstep;
       // operands of one group: i8 codes of 2 weight tiles and 2 token tiles, and their scales
@@ -214,9 +226,14 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
       // the next stage's unpack work is spread over the last four tile sweeps of this stage
       constexpr int NSTEP = GPS * 4;
       auto stage_piece = [&](int step) {
-        if (more_st && step >= NSTEP - 4) {
-          sstore_piece(buf ^ 1, step - (NSTEP - 4));
-          if (step == NSTEP - 1) sstore_piece(buf ^ 1, 4);   // scales
+        if (step >= NSTEP - 4) {                             // (after the last stage: unused)
+          const int i = step - (NSTEP - 4);
+          sstore_piece(buf ^ 1, i);
+          gload_piece(st2, i);
+          if (step == NSTEP - 1) {                           // scales
+            sstore_piece(buf ^ 1, 4);
+            gload_piece(st2, 4);
+          }
         }
       };
       load_ops(0);
