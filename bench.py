@@ -53,7 +53,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
-    ap.add_argument("--workload", default="flux", choices=["flux", "pixart", "small"])
+    ap.add_argument("--workload", default="flux", choices=["flux", "pixart", "small", "sweep", "ablation"],
+                    help="flux = the benchmark (configs[2]); pixart/small = configs[1]/[0]; sweep = token sweep "
+                         "(configs[3]); ablation = rank/group grid on the FLUX fc2 shape (configs[4])")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise copy of known size (256 MiB read + 256 MiB written), "
                          "the reference the FETCH_SIZE / WRITE_SIZE counters are scaled by")
@@ -75,7 +77,8 @@ def main() -> int:
     B.lib()                                           # fail loudly if the HIP library is not built
     torch.cuda.set_device(0)
     dev = "cuda"
-    shapes = {"flux": I.FLUX, "pixart": I.PIXART, "small": [I.SMALL]}[args.workload]
+    shapes = {"flux": I.FLUX, "pixart": I.PIXART, "small": [I.SMALL], "sweep": I.TOKEN_SWEEP,
+              "ablation": I.ABLATION}[args.workload]
 
     def dev_bf16(bits):
         return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
@@ -83,15 +86,24 @@ def main() -> int:
     # ---- inputs, resident in HBM before anything is timed ---------------------------
     layers = []
     t0 = time.time()
+    shared = None                                     # ablation: one set of draws for every (r, g)
     for shp in shapes:
-        L = I.make_layer(shp)
-        Q32 = torch.from_numpy(L.Q32).to(dev)
-        W = torch.from_numpy(L.W).to(dev)
-        Qt = B.prepare_rotation(Q32)
-        blob = B.prepare_weights(W, Q32, shp.r, shp.g)
-        x = dev_bf16(L.x_bits)
-        Wb = W.to(torch.bfloat16)                     # comparator: plain bf16 GEMM, same shape
-        del Q32, W
+        if args.workload == "ablation":
+            if shared is None:
+                L = I.make_layer(I.FLUX[3])            # same activations, basis and weights as flux_fc2
+                shared = (L, torch.from_numpy(L.Q32).to(dev), torch.from_numpy(L.W).to(dev))
+                shared += (B.prepare_rotation(shared[1]), dev_bf16(L.x_bits), shared[2].to(torch.bfloat16))
+            L, Q32, W, Qt, x, Wb = shared
+            blob = B.prepare_weights(W, Q32, shp.r, shp.g)
+        else:
+            L = I.make_layer(shp)
+            Q32 = torch.from_numpy(L.Q32).to(dev)
+            W = torch.from_numpy(L.W).to(dev)
+            Qt = B.prepare_rotation(Q32)
+            blob = B.prepare_weights(W, Q32, shp.r, shp.g)
+            x = dev_bf16(L.x_bits)
+            Wb = W.to(torch.bfloat16)                 # comparator: plain bf16 GEMM, same shape
+            del Q32, W
         ws = torch.empty(B.workspace_bytes(shp.M, shp.K, shp.r, shp.g), dtype=torch.uint8, device=dev)
         y = torch.empty((shp.M, shp.N), dtype=torch.bfloat16, device=dev)
         G = shp.G
@@ -159,6 +171,10 @@ def main() -> int:
         WbT = Ld["Wb"]
         yb = torch.empty_like(Ld["y"])
         tG = time_calls(lambda: torch.matmul(Ld["x"], WbT.t(), out=yb), reps)
+        # error of the quantized layer against the bf16 GEMM of the same operands (fp32 math on the GPU)
+        dlt = (Ld["y"].float() - yb.float())
+        rel_err = float(dlt.norm() / yb.float().norm())
+        del dlt
         per_layer.append({
             "layer": s.name, "M": s.M, "K": s.K, "N": s.N, "r": s.r, "g": s.g,
             "rotate_quantize_ms": round(tA[0], 4), "w4a4_gemm_ms": round(tB[0], 4), "linear_ms": round(tL[0], 4),
@@ -168,6 +184,8 @@ def main() -> int:
             "effective_tops": round(alg["layer_ops"] / (tL[0] * 1e-3) / 1e12, 2),
             "speedup_vs_bf16_gemm": round(tG[0] / tL[0], 4),
             "hbm_gbs_algorithmic": round((alg["A_bytes"] + alg["B_bytes"]) / (tL[0] * 1e-3) / 1e9, 1),
+            "rotate_quantize_share_of_layer": round(tA[0] / (tA[0] + tB[0]), 4),
+            "rel_err_vs_bf16_gemm": round(rel_err, 5),
             "_tA": tA[0], "_tB": tB[0], "_alg": alg,
         })
         log(f"{s.name}: A {tA[0]:.3f} ms  B {tB[0]:.3f} ms  fused {tL[0]:.3f} ms  bf16 GEMM {tG[0]:.3f} ms")
@@ -242,7 +260,9 @@ def main() -> int:
                                         "r=128, g=64: fused QKV (N=9216), out-proj (N=3072), fc1 (N=12288), "
                                         "fc2 (K=12288, N=3072); one dirotq_linear per layer per step",
                                 "pixart": "configs[1]: PixArt-Sigma-shaped block linears, M=4096",
-                                "small": "configs[0]: M=256, K=N=1152"}[args.workload],
+                                "small": "configs[0]: M=256, K=N=1152",
+                                "sweep": "configs[3]: token sweep on the PixArt fc1 shape, M in {1024..32768}",
+                                "ablation": "configs[4]: rank/group grid on the FLUX fc2 shape"}[args.workload],
                    "seed": 0, "effective_ops_per_step": total_ops},
         "speedup_vs_bf16_gemm": round(bf16_ms / ms_per_step, 4),
         "bf16_gemm_ms_per_step": round(bf16_ms, 4),

@@ -52,7 +52,7 @@ template <int WGC, int WGT, int BK, int NBUF, bool DMA, bool PF>
 __global__ __launch_bounds__(WGC* WGT * 64, 2) void rotate_quantize_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ Qt, int M, int K, int r, int g,
     uint16_t* __restrict__ xh, uint8_t* __restrict__ xl, uint16_t* __restrict__ sx, int r_pad, int Kv, int n_ct,
-    int n_tt, int per_xcd) {
+    int n_tt, int per_xcd, int sx_ld) {
   using C = RQ<WGC, WGT, BK, NBUF>;
   extern __shared__ __align__(16) unsigned char smem[];
 
@@ -244,7 +244,7 @@ __global__ __launch_bounds__(WGC* WGT * 64, 2) void rotate_quantize_kernel(
       uint16_t sbits;
       const float sf = group_scale(tmax[i], sbits);
       const float inv = group_inv(sf);
-      if (valid && h == 0 && (i % gi_tiles) == 0) sx[(size_t)(cl / g) * M + m] = sbits;
+      if (valid && h == 0 && (i % gi_tiles) == 0) sx[(size_t)(cl / g) * sx_ld + m] = sbits;
       // this lane's 16 codes: quad q covers channels cl + 8q + 4h .. +3 -> one 16-bit piece
       uint32_t piece[4];
 #pragma unroll
@@ -268,7 +268,13 @@ __global__ __launch_bounds__(WGC* WGT * 64, 2) void rotate_quantize_kernel(
 
 template <int WGC, int WGT, int BK, int NBUF, bool DMA = true, bool PF = false>
 static int launch_cfg(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g, uint16_t* xh,
-                      uint8_t* xl, uint16_t* sx, hipStream_t s) {
+                      uint8_t* xl, uint16_t* sx, hipStream_t s, int m_off = 0, int sx_ld = 0) {
+  // tokens [m_off, m_off + M) of the caller's arrays; sx_ld = total token count (row length of s_x)
+  if (sx_ld == 0) sx_ld = M;
+  x += (size_t)m_off * K;
+  if (xh) xh += (size_t)m_off * r;
+  if (xl) xl += (size_t)m_off * ((K - r) / 2);
+  if (sx) sx += m_off;
   using C = RQ<WGC, WGT, BK, NBUF>;
   const int r_pad = (r + 127) / 128 * 128;
   const int Kv = r_pad + (K - r + 127) / 128 * 128;
@@ -284,7 +290,7 @@ static int launch_cfg(const uint16_t* x, const uint16_t* Qt, int M, int K, int r
     attr_done = true;
   }
   hipLaunchKernelGGL((rotate_quantize_kernel<WGC, WGT, BK, NBUF, DMA, PF>), dim3(per_xcd * 8), dim3(C::NT), C::SMEM, s, x,
-                     Qt, M, K, r, g, xh, xl, sx, r_pad, Kv, n_ct, n_tt, per_xcd);
+                     Qt, M, K, r, g, xh, xl, sx, r_pad, Kv, n_ct, n_tt, per_xcd, sx_ld);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? DIROTQ_OK : hip_failed(e);
 }
@@ -302,7 +308,19 @@ int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, 
   return launch_cfg<DIROTQ_RQ_FORCE>(x, Qt, M, K, r, g, xh, xl, sx, s);
 #endif
   if (K % 64 != 0) return launch_cfg<1, 2, 32, 4>(x, Qt, M, K, r, g, xh, xl, sx, s);
-  if (big_tiles >= 200) return launch_cfg<2, 4, 64, 2, true, true>(x, Qt, M, K, r, g, xh, xl, sx, s);
+  if (big_tiles >= 200) {
+    // 256 CUs take one big tile each per round.  When the last round would be less than ~60%
+    // full, the tokens of that round are done with half-size tiles in a second launch instead,
+    // so that they spread over the whole chip.
+    const long full = big_tiles / 256 * 256, tail = big_tiles - full;
+    const int tt_big = (int)(full / n_tc256);               // token tiles covered by full rounds
+    if (full > 0 && tail > 0 && tail < 160 && tt_big * 256 < M && (M - tt_big * 256) % 128 == 0) {
+      int st = launch_cfg<2, 4, 64, 2, true, true>(x, Qt, tt_big * 256, K, r, g, xh, xl, sx, s, 0, M);
+      if (st) return st;
+      return launch_cfg<2, 2, 64, 2, true, true>(x, Qt, M - tt_big * 256, K, r, g, xh, xl, sx, s, tt_big * 256, M);
+    }
+    return launch_cfg<2, 4, 64, 2, true, true>(x, Qt, M, K, r, g, xh, xl, sx, s);
+  }
   if (mid_tiles >= 100) return launch_cfg<2, 2, 64, 2>(x, Qt, M, K, r, g, xh, xl, sx, s);
   return launch_cfg<1, 2, 64, 2>(x, Qt, M, K, r, g, xh, xl, sx, s);
 }
