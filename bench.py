@@ -56,6 +56,8 @@ def main() -> int:
     ap.add_argument("--workload", default="flux", choices=["flux", "pixart", "small", "sweep", "ablation"],
                     help="flux = the benchmark (configs[2]); pixart/small = configs[1]/[0]; sweep = token sweep "
                          "(configs[3]); ablation = rank/group grid on the FLUX fc2 shape (configs[4])")
+    ap.add_argument("--residual-rotation", action="store_true",
+                    help="fold a random orthogonal rotation of the 4-bit subspace into Q (Q = [U_h, U_l R])")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise copy of known size (256 MiB read + 256 MiB written), "
                          "the reference the FETCH_SIZE / WRITE_SIZE counters are scaled by")
@@ -90,13 +92,13 @@ def main() -> int:
     for shp in shapes:
         if args.workload == "ablation":
             if shared is None:
-                L = I.make_layer(I.FLUX[3])            # same activations, basis and weights as flux_fc2
+                L = I.make_layer(I.FLUX[3], residual_rotation=args.residual_rotation)   # same draws as flux_fc2
                 shared = (L, torch.from_numpy(L.Q32).to(dev), torch.from_numpy(L.W).to(dev))
                 shared += (B.prepare_rotation(shared[1]), dev_bf16(L.x_bits), shared[2].to(torch.bfloat16))
             L, Q32, W, Qt, x, Wb = shared
             blob = B.prepare_weights(W, Q32, shp.r, shp.g)
         else:
-            L = I.make_layer(shp)
+            L = I.make_layer(shp, residual_rotation=args.residual_rotation)
             Q32 = torch.from_numpy(L.Q32).to(dev)
             W = torch.from_numpy(L.W).to(dev)
             Qt = B.prepare_rotation(Q32)
@@ -263,7 +265,7 @@ def main() -> int:
                                 "small": "configs[0]: M=256, K=N=1152",
                                 "sweep": "configs[3]: token sweep on the PixArt fc1 shape, M in {1024..32768}",
                                 "ablation": "configs[4]: rank/group grid on the FLUX fc2 shape"}[args.workload],
-                   "seed": 0, "effective_ops_per_step": total_ops},
+                   "seed": 0, "effective_ops_per_step": total_ops, "residual_rotation": args.residual_rotation},
         "speedup_vs_bf16_gemm": round(bf16_ms / ms_per_step, 4),
         "bf16_gemm_ms_per_step": round(bf16_ms, 4),
         "roofline": {k: (round(v, 5) if isinstance(v, float) else v) for k, v in roofline.items()},

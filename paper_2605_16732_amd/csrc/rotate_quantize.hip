@@ -39,16 +39,21 @@ struct RQ {
   static constexpr int IPW = (TC + TT) * CPR / 64 / NW;    // load instructions per wave per stage
   static constexpr int SMEM = NBUF * STAGE_BYTES;
   static_assert((TC + TT) * CPR % (64 * NW) == 0, "loads must divide evenly over waves");
-  static_assert(BK == 32 || BK == 64, "BK");
+  static_assert(BK == 32 || BK == 48 || BK == 64, "BK");
   static_assert(NBUF >= 2 && NBUF <= 4, "NBUF");
 
   // chunk c of row `row` is stored in 16-B slot c ^ swz(row)
   // (LDS has 64 banks: a 16-byte read is served 16 lanes per cycle, so 16 consecutive rows
   // must land in 16 different 16-byte slots of a 256-byte bank line)
-  __device__ static __forceinline__ int swz(int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
+  // 128-byte rows (BK = 64): row&1 picks the half line, (row>>1)&7 permutes the 8 chunks;
+  // 96-byte rows (BK = 48): 6 r mod 16 repeats every 8 rows, so rows r and r+8 swap chunk pairs;
+  // 64-byte rows (BK = 32): row&3 picks the quarter line, (row>>2)&3 permutes the 4 chunks.
+  __device__ static __forceinline__ int swz(int row) {
+    return BK == 64 ? ((row >> 1) & 7) : BK == 48 ? ((row >> 3) & 1) : ((row >> 2) & 3);
+  }
 };
 
-template <int WGC, int WGT, int BK, int NBUF, bool DMA, bool PF>
+template <int WGC, int WGT, int BK, int NBUF, bool PF>
 __global__ __launch_bounds__(WGC* WGT * 64, 2) void rotate_quantize_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ Qt, int M, int K, int r, int g,
     uint16_t* __restrict__ xh, uint8_t* __restrict__ xl, uint16_t* __restrict__ sx, int r_pad, int Kv, int n_ct,
@@ -97,18 +102,6 @@ __global__ __launch_bounds__(WGC* WGT * 64, 2) void rotate_quantize_kernel(
                                        (lds_void*)(smem + buf * C::STAGE_BYTES + (w * C::IPW + i) * 1024), 16, 0,
                                        0);
   };
-  // alternative staging through registers (same LDS image)
-  uint4 stg[DMA ? 1 : C::IPW];
-  auto gload = [&](int kt) {
-#pragma unroll
-    for (int i = 0; i < C::IPW; i++) stg[DMA ? 0 : i] = *(const uint4*)(gsrc[i] + kt * BK);
-  };
-  auto sstore = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < C::IPW; i++)
-      *(uint4*)(smem + buf * C::STAGE_BYTES + (w * C::IPW + i) * 1024 + l * 16) = stg[DMA ? 0 : i];
-  };
-
   f32x16 acc[4][2];
 #pragma unroll
   for (int i = 0; i < 4; i++)
@@ -166,29 +159,17 @@ __global__ __launch_bounds__(WGC* WGT * 64, 2) void rotate_quantize_kernel(
       }
     }
   };
-  if constexpr (DMA) {
 #pragma unroll
-    for (int s = 0; s < NBUF - 1; s++)
-      if (s < nk) issue(s, s);
-    for (int kt = 0; kt < nk; kt++) {
-      const int rem = nk - 1 - kt;                          // stages issued after stage kt
-      if (NBUF >= 4 && rem >= 2) wait_vmcnt<2 * C::IPW>();
-      else if (NBUF >= 3 && rem >= 1) wait_vmcnt<1 * C::IPW>();
-      else wait_vmcnt<0>();
-      __syncthreads();
-      if (kt + NBUF - 1 < nk) issue(kt + NBUF - 1, (kt + NBUF - 1) % NBUF);
-      compute(smem + (kt % NBUF) * C::STAGE_BYTES);
-    }
-  } else {
-    gload(0);
-    sstore(0);
+  for (int s = 0; s < NBUF - 1; s++)
+    if (s < nk) issue(s, s);
+  for (int kt = 0; kt < nk; kt++) {
+    const int rem = nk - 1 - kt;                            // stages issued after stage kt
+    if (NBUF >= 4 && rem >= 2) wait_vmcnt<2 * C::IPW>();
+    else if (NBUF >= 3 && rem >= 1) wait_vmcnt<1 * C::IPW>();
+    else wait_vmcnt<0>();
     __syncthreads();
-    for (int kt = 0; kt < nk; kt++) {
-      if (kt + 1 < nk) gload(kt + 1);
-      compute(smem + (kt & 1) * C::STAGE_BYTES);
-      if (kt + 1 < nk) sstore((kt + 1) & 1);
-      __syncthreads();
-    }
+    if (kt + NBUF - 1 < nk) issue(kt + NBUF - 1, (kt + NBUF - 1) % NBUF);
+    compute(smem + (kt % NBUF) * C::STAGE_BYTES);
   }
 
   // ---- epilogue, in registers ------------------------------------------------------
@@ -266,7 +247,7 @@ __global__ __launch_bounds__(WGC* WGT * 64, 2) void rotate_quantize_kernel(
   }
 }
 
-template <int WGC, int WGT, int BK, int NBUF, bool DMA = true, bool PF = false>
+template <int WGC, int WGT, int BK, int NBUF, bool PF = false>
 static int launch_cfg(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g, uint16_t* xh,
                       uint8_t* xl, uint16_t* sx, hipStream_t s, int m_off = 0, int sx_ld = 0) {
   // tokens [m_off, m_off + M) of the caller's arrays; sx_ld = total token count (row length of s_x)
@@ -284,12 +265,12 @@ static int launch_cfg(const uint16_t* x, const uint16_t* Qt, int M, int K, int r
   const int per_xcd = (int)((n_blocks + 7) / 8);
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)rotate_quantize_kernel<WGC, WGT, BK, NBUF, DMA, PF>,
+    hipError_t e = hipFuncSetAttribute((const void*)rotate_quantize_kernel<WGC, WGT, BK, NBUF, PF>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
     if (e != hipSuccess) return hip_failed(e);
     attr_done = true;
   }
-  hipLaunchKernelGGL((rotate_quantize_kernel<WGC, WGT, BK, NBUF, DMA, PF>), dim3(per_xcd * 8), dim3(C::NT), C::SMEM, s, x,
+  hipLaunchKernelGGL((rotate_quantize_kernel<WGC, WGT, BK, NBUF, PF>), dim3(per_xcd * 8), dim3(C::NT), C::SMEM, s, x,
                      Qt, M, K, r, g, xh, xl, sx, r_pad, Kv, n_ct, n_tt, per_xcd, sx_ld);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? DIROTQ_OK : hip_failed(e);
@@ -304,7 +285,7 @@ int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, 
   const long n_tc256 = (Kv + 255) / 256;
   const long big_tiles = n_tc256 * ((M + 255) / 256);    // 256 channels x 256 tokens
   const long mid_tiles = n_tc256 * ((M + 127) / 128);    // 256 channels x 128 tokens
-#ifdef DIROTQ_RQ_FORCE   // build-time tuning aid: -DDIROTQ_RQ_FORCE=WGC,WGT,BK,NBUF
+#ifdef DIROTQ_RQ_FORCE   // build-time tuning aid: -DDIROTQ_RQ_FORCE=WGC,WGT,BK,NBUF[,PF]
   return launch_cfg<DIROTQ_RQ_FORCE>(x, Qt, M, K, r, g, xh, xl, sx, s);
 #endif
   if (K % 64 != 0) return launch_cfg<1, 2, 32, 4>(x, Qt, M, K, r, g, xh, xl, sx, s);
@@ -315,11 +296,11 @@ int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, 
     const long full = big_tiles / 256 * 256, tail = big_tiles - full;
     const int tt_big = (int)(full / n_tc256);               // token tiles covered by full rounds
     if (full > 0 && tail > 0 && tail < 160 && tt_big * 256 < M && (M - tt_big * 256) % 128 == 0) {
-      int st = launch_cfg<2, 4, 64, 2, true, true>(x, Qt, tt_big * 256, K, r, g, xh, xl, sx, s, 0, M);
+      int st = launch_cfg<2, 4, 64, 2, true>(x, Qt, tt_big * 256, K, r, g, xh, xl, sx, s, 0, M);
       if (st) return st;
-      return launch_cfg<2, 2, 64, 2, true, true>(x, Qt, M - tt_big * 256, K, r, g, xh, xl, sx, s, tt_big * 256, M);
+      return launch_cfg<2, 2, 64, 2, true>(x, Qt, M - tt_big * 256, K, r, g, xh, xl, sx, s, tt_big * 256, M);
     }
-    return launch_cfg<2, 4, 64, 2, true, true>(x, Qt, M, K, r, g, xh, xl, sx, s);
+    return launch_cfg<2, 4, 64, 2, true>(x, Qt, M, K, r, g, xh, xl, sx, s);
   }
   if (mid_tiles >= 100) return launch_cfg<2, 2, 64, 2>(x, Qt, M, K, r, g, xh, xl, sx, s);
   return launch_cfg<1, 2, 64, 2>(x, Qt, M, K, r, g, xh, xl, sx, s);

@@ -207,16 +207,19 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
       i32x16 I[2];
       f32x16 P[2];
       auto issue = [&](int i, int j, int slot) {     // 256 I and the scale product of tile (i, j)
+        // the scale-product MFMA sits between the first two (dependent) integer MFMAs, so the
+        // second one finds its accumulator ready instead of stalling the wave at issue
         i32x16 z;
 #pragma unroll
         for (int v = 0; v < 16; v++) z[v] = 0;
-#pragma unroll
-        for (int kk = 0; kk < MPG; kk++) z = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i][kk], b[j][kk], z, 0, 0, 0);
-        I[slot] = z;
+        z = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i][0], b[j][0], z, 0, 0, 0);
         f32x16 p;
 #pragma unroll
         for (int v = 0; v < 16; v++) p[v] = 0.0f;
         P[slot] = __builtin_amdgcn_mfma_f32_32x32x8f16(sa[i], sbv[j], p, 0, 0, 0);
+#pragma unroll
+        for (int kk = 1; kk < MPG; kk++) z = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i][kk], b[j][kk], z, 0, 0, 0);
+        I[slot] = z;
       };
       auto sweep = [&](int i, int j, int slot) {     // acc += float(256 I) * P for tile (i, j)
 #pragma unroll
@@ -236,33 +239,46 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
           }
         }
       };
+      // One pipeline step = the MFMAs of the next tile interleaved with the convert/fma sweep of
+      // the current one (so that neither the matrix pipe nor the vector ALU waits for the other
+      // inside a wave): 1 MFMA, then a share of the VALU work, repeated.
+      auto interleave = [&](bool valu_first) {
+        constexpr int NM = MPG + 1, PER = 32 / NM;
+        if (valu_first) __builtin_amdgcn_sched_group_barrier(0x002, PER, 0);
+#pragma unroll
+        for (int q = 0; q < NM; q++) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
+          __builtin_amdgcn_sched_group_barrier(0x002, PER, 0);    // PER VALU instructions
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      };
       load_ops(0);
       issue(0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int jj = 0; jj < GPS; jj++) {
         const bool more = jj + 1 < GPS;              // compile-time after unrolling
         issue(0, 1, 1);
-        __builtin_amdgcn_sched_barrier(0);
         sweep(0, 0, 0);
         stage_piece(jj * 4 + 0);
-        __builtin_amdgcn_sched_barrier(0);
+        interleave(false);
         issue(1, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
         sweep(0, 1, 1);
         stage_piece(jj * 4 + 1);
-        __builtin_amdgcn_sched_barrier(0);
+        interleave(false);
         issue(1, 1, 1);
-        asm volatile("" ::: "memory");               // keep the next group's LDS reads below this point
-        if (more) load_ops(jj + 1);                  // every MFMA of this group is issued
-        __builtin_amdgcn_sched_barrier(0);
         sweep(1, 0, 0);
         stage_piece(jj * 4 + 2);
-        __builtin_amdgcn_sched_barrier(0);
-        if (more) issue(0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
+        interleave(false);
+        asm volatile("" ::: "memory");               // keep the next group's LDS reads below this point
+        if (more) {
+          load_ops(jj + 1);                          // every MFMA of this group is issued
+          __builtin_amdgcn_sched_barrier(0);
+          issue(0, 0, 0);
+        }
         sweep(1, 1, 1);
         stage_piece(jj * 4 + 3);
-        __builtin_amdgcn_sched_barrier(0);
+        interleave(true);     // the fresh LDS operands get a few VALU slots to arrive
       }
       __syncthreads();
     }

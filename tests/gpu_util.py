@@ -103,13 +103,13 @@ def check_output(y_gpu: np.ndarray, y32: np.ndarray, tol=1e-2):
 _layer_cache: dict = {}
 
 
-def layer_with_oracle(shape: I.LayerShape, M: int | None = None, rows=None):
+def layer_with_oracle(shape: I.LayerShape, M: int | None = None, rows=None, residual_rotation: bool = False):
     """Inputs of a layer plus the oracle's full result (cached per shape).  `rows`
     selects a subset of tokens for the oracle (tokens are independent)."""
-    key = (shape, M, None if rows is None else tuple(rows))
+    key = (shape, M, None if rows is None else tuple(rows), residual_rotation)
     if key in _layer_cache:
         return _layer_cache[key]
-    L = I.make_layer(shape, M=M)
+    L = I.make_layer(shape, M=M, residual_rotation=residual_rotation)
     x = I.bf16_bits_to_f32(L.x_bits)
     Q = I.bf16_bits_to_f32(L.Q_bits)
     Wh, qw, sw = O.prepare_weights(L.W, L.Q32, shape.r, shape.g)

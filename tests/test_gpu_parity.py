@@ -195,8 +195,8 @@ def test_w4a4_gemm_matches_oracle_on_identical_inputs(M, N, K, r, g, use_bias):
 
 
 # ------------------------------------------------------------------ end to end
-def _end_to_end(shape, M=None, rows=None):
-    L, (Wh, qw, sw), ref = layer_with_oracle(shape, M=M, rows=rows)
+def _end_to_end(shape, M=None, rows=None, residual_rotation=False):
+    L, (Wh, qw, sw), ref = layer_with_oracle(shape, M=M, rows=rows, residual_rotation=residual_rotation)
     Mx, K, N, r, g = L.x_bits.shape[0], shape.K, shape.N, shape.r, shape.g
     Qt = B.prepare_rotation(dev(L.Q32))
     np.testing.assert_array_equal(host_bf16_bits(Qt), np.ascontiguousarray(L.Q_bits.T))
@@ -272,6 +272,21 @@ def test_end_to_end_rank_group_grid(r, g):
     # the (r, g) pairs of the rank/group ablation, on a reduced fc2-like shape with a ragged M
     shp = I.LayerShape(f"abl_r{r}_g{g}", 200, 1536, 384, r, g, 8, 8, r * 4 + g)
     _end_to_end(shp)
+
+
+def test_end_to_end_with_residual_rotation():
+    """Q = [U_h, U_l R] with a random orthogonal R on the 4-bit subspace (Section 4.2): a data
+    variant of the same kernels.  R equalises the 4-bit channels, so the oracle's own error
+    against the unquantized product must not get worse."""
+    shp = I.LayerShape("resrot", 384, 768, 512, 64, 64, 8, 8, 77)
+    _end_to_end(shp, residual_rotation=True)
+    errs = {}
+    for rr in (False, True):
+        L, (Wh, qw, sw), ref = layer_with_oracle(shp, residual_rotation=rr)
+        x = I.bf16_bits_to_f32(L.x_bits).astype(np.float64)
+        errs[rr] = O.qsnr_db(x @ L.W.astype(np.float64).T, ref["y32"])
+    _say(f"QSNR vs unquantized product: PCA only {errs[False]:.2f} dB, PCA + R {errs[True]:.2f} dB")
+    assert errs[True] > errs[False] - 0.5
 
 
 def test_rank_equals_K_is_a_bf16_gemm():
