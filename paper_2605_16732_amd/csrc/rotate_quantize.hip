@@ -13,22 +13,18 @@
 // Channel tiling.  Waves own 128 "virtual" channels: the bf16 part [0, r) is padded to a
 // multiple of 128, the 4-bit part [r, K) follows, so groups never straddle a wave.
 //
-// Main loop.  Operand tiles go HBM -> LDS directly (global_load_lds, 16 B per lane),
-// NBUF stages deep, with an XOR swizzle applied on the global side so that the 16-byte
-// MFMA operand reads of 16 consecutive rows are bank-conflict free.
+// Main loop.  Operand tiles are staged HBM -> registers -> LDS (two LDS stages) with an
+// XOR swizzle applied on the global side, so that the 16-byte MFMA operand reads of 16
+// consecutive rows are bank-conflict free.  While stage kt is multiplied, the registers
+// holding stage kt+1 (loaded during stage kt-1) are written to the other LDS stage and
+// refilled with stage kt+2; every store/load pair sits between MFMAs.  (On gfx950 this
+// beats the direct global_load_lds path: those instructions hold up the matrix pipe of the
+// issuing SIMD far longer than a register load plus an LDS store.)
 #include "dirotq_internal.h"
 
 namespace dirotq {
 
-typedef __attribute__((address_space(3))) void lds_void;
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  // gfx9 s_waitcnt: vmcnt = imm[3:0] | imm[15:14]<<4, expcnt = imm[6:4], lgkmcnt = imm[11:8]
-  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
-}
-
-template <int WGC, int WGT, int BK, int NBUF>
+template <int WGC, int WGT, int BK>
 struct RQ {
   static constexpr int WAVE_C = 128, WAVE_T = 64;          // wave tile: channels x tokens
   static constexpr int TC = WGC * WAVE_C, TT = WGT * WAVE_T;
@@ -36,29 +32,31 @@ struct RQ {
   static constexpr int ROWB = BK * 2;                      // bytes per LDS row
   static constexpr int CPR = ROWB / 16;                    // 16-B chunks per row
   static constexpr int STAGE_BYTES = (TC + TT) * ROWB;
-  static constexpr int IPW = (TC + TT) * CPR / 64 / NW;    // load instructions per wave per stage
-  static constexpr int SMEM = NBUF * STAGE_BYTES;
+  static constexpr int IPW = (TC + TT) * CPR / 64 / NW;    // 16-B loads per lane per stage
+  static constexpr int KS = BK / 16;                       // MFMA k-steps per stage
+  static constexpr int PP = IPW / KS;                      // store/load pairs per k-step
+  static constexpr int SMEM = 2 * STAGE_BYTES;
+  // register budget: two waves per SIMD unless LDS (160 KB per CU) admits only one 4-wave workgroup
+  static constexpr int WAVES_PER_SIMD = (NW <= 4 && 2 * SMEM > 160 * 1024) ? 1 : 2;
   static_assert((TC + TT) * CPR % (64 * NW) == 0, "loads must divide evenly over waves");
-  static_assert(BK == 32 || BK == 48 || BK == 64, "BK");
-  static_assert(NBUF >= 2 && NBUF <= 4, "NBUF");
+  static_assert(BK == 32 || BK == 64, "BK");
+  static_assert(IPW % KS == 0 && PP >= 1 && PP <= 4, "store/load pairs are spread over the 4 MFMA rows of a k-step");
 
   // chunk c of row `row` is stored in 16-B slot c ^ swz(row)
   // (LDS has 64 banks: a 16-byte read is served 16 lanes per cycle, so 16 consecutive rows
   // must land in 16 different 16-byte slots of a 256-byte bank line)
   // 128-byte rows (BK = 64): row&1 picks the half line, (row>>1)&7 permutes the 8 chunks;
-  // 96-byte rows (BK = 48): 6 r mod 16 repeats every 8 rows, so rows r and r+8 swap chunk pairs;
   // 64-byte rows (BK = 32): row&3 picks the quarter line, (row>>2)&3 permutes the 4 chunks.
-  __device__ static __forceinline__ int swz(int row) {
-    return BK == 64 ? ((row >> 1) & 7) : BK == 48 ? ((row >> 3) & 1) : ((row >> 2) & 3);
-  }
+  __device__ static __forceinline__ int swz(int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
 };
 
-template <int WGC, int WGT, int BK, int NBUF, bool PF>
-__global__ __launch_bounds__(WGC* WGT * 64, 2) void rotate_quantize_kernel(
+template <int WGC, int WGT, int BK>
+__global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK>::WAVES_PER_SIMD)) void rotate_quantize_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ Qt, int M, int K, int r, int g,
     uint16_t* __restrict__ xh, uint8_t* __restrict__ xl, uint16_t* __restrict__ sx, int r_pad, int Kv, int n_ct,
     int n_tt, int per_xcd, int sx_ld) {
-  using C = RQ<WGC, WGT, BK, NBUF>;
+  using C = RQ<WGC, WGT, BK>;
+  constexpr int WT = 2;                                     // 32-token MFMA tiles per wave
   extern __shared__ __align__(16) unsigned char smem[];
 
   // consecutive workgroup ids go to different XCDs; give each XCD a contiguous run of tiles
@@ -75,9 +73,10 @@ __global__ __launch_bounds__(WGC* WGT * 64, 2) void rotate_quantize_kernel(
   const int t = threadIdx.x, l = t & 63, w = t >> 6;
   const int wc = w % WGC, wt = w / WGC;
 
-  // ---- per-lane source pointers of this wave's load instructions --------------------
-  // instruction i of wave w fills LDS bytes [(w*IPW+i)*1024, +1024) of a stage: rows are
-  // the TC channel rows followed by the TT token rows.
+  // ---- per-lane source pointers of this wave's loads ---------------------------------
+  // load q of wave w fills LDS bytes [(w*IPW+q)*1024, +1024) of a stage: rows are the TC
+  // channel rows followed by the TT token rows.  Rows past the edge re-read a valid row; their
+  // results are discarded in the epilogue.
   const uint16_t* gsrc[C::IPW];
 #pragma unroll
   for (int i = 0; i < C::IPW; i++) {
@@ -95,81 +94,75 @@ __global__ __launch_bounds__(WGC* WGT * 64, 2) void rotate_quantize_kernel(
     }
     gsrc[i] = base + logical_chunk * 8;
   }
-  auto issue = [&](int kt, int buf) {      // HBM -> LDS, one stage, asynchronous
-#pragma unroll
-    for (int i = 0; i < C::IPW; i++)
-      __builtin_amdgcn_global_load_lds((const void*)(gsrc[i] + kt * BK),
-                                       (lds_void*)(smem + buf * C::STAGE_BYTES + (w * C::IPW + i) * 1024), 16, 0,
-                                       0);
+  i32x4 staged[C::IPW];
+  auto gload = [&](int q, int kt) { staged[q] = *(const i32x4*)(gsrc[q] + kt * BK); };
+  auto swrite = [&](int q, int buf) {
+    *(i32x4*)(smem + buf * C::STAGE_BYTES + (w * C::IPW + q) * 1024 + l * 16) = staged[q];
   };
-  f32x16 acc[4][2];
+
+  f32x16 acc[4][WT];
 #pragma unroll
   for (int i = 0; i < 4; i++)
 #pragma unroll
-    for (int j = 0; j < 2; j++)
+    for (int j = 0; j < WT; j++)
 #pragma unroll
       for (int v = 0; v < 16; v++) acc[i][j][v] = 0.0f;
 
   // operand read offsets (bytes within a stage) for k-step 0; k-step ks flips chunk bits
-  int offA[4], offB[2];
+  int offA[4], offB[WT];
 #pragma unroll
   for (int i = 0; i < 4; i++) offA[i] = (wc * 128 + i * 32 + (l & 31)) * C::ROWB;
 #pragma unroll
-  for (int j = 0; j < 2; j++) offB[j] = (C::TC + wt * 64 + j * 32 + (l & 31)) * C::ROWB;
+  for (int j = 0; j < WT; j++) offB[j] = (C::TC + wt * C::WAVE_T + j * 32 + (l & 31)) * C::ROWB;
   const int swzA = C::swz(l & 31), swzB = C::swz(l & 31);   // tile bases are multiples of 32 rows
 
   const int nk = K / BK;                                    // the launcher guarantees K % BK == 0
-  auto compute = [&](const unsigned char* sb) {
-    if constexpr (PF) {
-      // operands of k-step ks+1 are fetched from LDS while the MFMAs of k-step ks run
-      bf16x8 a[2][4], b[2][2];
-      auto lds_fetch = [&](int ks, int slot) {
-        const int chunk = 2 * ks + (l >> 5);
+  // prologue: stage 0 into LDS, stage 1 into the registers.  Loads past the last stage re-read
+  // it: unconditional loads keep the outstanding-load count the same in every iteration, so
+  // the waits the compiler derives are exact.
 #pragma unroll
-        for (int i = 0; i < 4; i++) a[slot][i] = *(const bf16x8*)(sb + offA[i] + ((chunk ^ swzA) << 4));
+  for (int q = 0; q < C::IPW; q++) gload(q, 0);
 #pragma unroll
-        for (int j = 0; j < 2; j++) b[slot][j] = *(const bf16x8*)(sb + offB[j] + ((chunk ^ swzB) << 4));
-      };
-      lds_fetch(0, 0);
+  for (int q = 0; q < C::IPW; q++) {
+    swrite(q, 0);
+    gload(q, min(1, nk - 1));
+  }
+  __syncthreads();
+  bf16x8 a[2][4], b[2][WT];
+  for (int kt = 0; kt < nk; kt++) {
+    const unsigned char* sb = smem + (kt & 1) * C::STAGE_BYTES;
+    const int wbuf = (kt + 1) & 1, kt_load = min(kt + 2, nk - 1);
+    // operands of k-step ks+1 are fetched from LDS while the MFMAs of k-step ks run
+    auto lds_fetch = [&](int ks, int slot) {
+      const int chunk = 2 * ks + (l >> 5);
 #pragma unroll
-      for (int ks = 0; ks < BK / 16; ks++) {
-        if (ks + 1 < BK / 16) lds_fetch(ks + 1, (ks + 1) & 1);
-        __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads ahead of this k-step's MFMAs
+      for (int i = 0; i < 4; i++) a[slot][i] = *(const bf16x8*)(sb + offA[i] + ((chunk ^ swzA) << 4));
 #pragma unroll
-        for (int i = 0; i < 4; i++)
+      for (int j = 0; j < WT; j++) b[slot][j] = *(const bf16x8*)(sb + offB[j] + ((chunk ^ swzB) << 4));
+    };
+    lds_fetch(0, 0);
 #pragma unroll
-          for (int j = 0; j < 2; j++)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][i], b[ks & 1][j], acc[i][j], 0, 0, 0);
+    for (int ks = 0; ks < C::KS; ks++) {
+      const int cur = ks & 1;
+      int pair = 0;
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+#pragma unroll
+        for (int j = 0; j < WT; j++)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (i == 0 && ks + 1 < C::KS) lds_fetch(ks + 1, cur ^ 1);
+        // the PP store/load pairs of this k-step, spread over its four MFMA rows
+        if (pair < C::PP && i >= (pair * 4) / C::PP) {
+          const int q = ks * C::PP + pair;
+          swrite(q, wbuf);
+          gload(q, kt_load);
+          pair++;
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
-    } else {
-#pragma unroll
-      for (int ks = 0; ks < BK / 16; ks++) {
-        const int chunk = 2 * ks + (l >> 5);
-        bf16x8 a[4], b[2];
-#pragma unroll
-        for (int i = 0; i < 4; i++) a[i] = *(const bf16x8*)(sb + offA[i] + ((chunk ^ swzA) << 4));
-#pragma unroll
-        for (int j = 0; j < 2; j++) b[j] = *(const bf16x8*)(sb + offB[j] + ((chunk ^ swzB) << 4));
-#pragma unroll
-        for (int i = 0; i < 4; i++)
-#pragma unroll
-          for (int j = 0; j < 2; j++)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-      }
     }
-  };
-#pragma unroll
-  for (int s = 0; s < NBUF - 1; s++)
-    if (s < nk) issue(s, s);
-  for (int kt = 0; kt < nk; kt++) {
-    const int rem = nk - 1 - kt;                            // stages issued after stage kt
-    if (NBUF >= 4 && rem >= 2) wait_vmcnt<2 * C::IPW>();
-    else if (NBUF >= 3 && rem >= 1) wait_vmcnt<1 * C::IPW>();
-    else wait_vmcnt<0>();
-    __syncthreads();
-    if (kt + NBUF - 1 < nk) issue(kt + NBUF - 1, (kt + NBUF - 1) % NBUF);
-    compute(smem + (kt % NBUF) * C::STAGE_BYTES);
+    __syncthreads();   // stage kt+1 is complete in LDS; stage kt may be overwritten
   }
 
   // ---- epilogue, in registers ------------------------------------------------------
@@ -179,8 +172,8 @@ __global__ __launch_bounds__(WGC* WGT * 64, 2) void rotate_quantize_kernel(
   if (vb < r_pad) {
     // 16-bit part: 4 consecutive channels per register quad -> one 8-byte store
 #pragma unroll
-    for (int j = 0; j < 2; j++) {
-      const int m = m0 + wt * 64 + j * 32 + (l & 31);
+    for (int j = 0; j < WT; j++) {
+      const int m = m0 + wt * C::WAVE_T + j * 32 + (l & 31);
 #pragma unroll
       for (int i = 0; i < 4; i++)
 #pragma unroll
@@ -201,8 +194,8 @@ __global__ __launch_bounds__(WGC* WGT * 64, 2) void rotate_quantize_kernel(
   const size_t xl_ld = (size_t)KL / 2;
   const int gi_tiles = g >> 5;                              // 32-channel MFMA tiles per group: 1, 2, 4
 #pragma unroll
-  for (int j = 0; j < 2; j++) {
-    const int m = m0 + wt * 64 + j * 32 + (l & 31);
+  for (int j = 0; j < WT; j++) {
+    const int m = m0 + wt * C::WAVE_T + j * 32 + (l & 31);
     // absmax of each 32-channel tile over the lane pair, then combined per group
     float tmax[4];
 #pragma unroll
@@ -247,7 +240,7 @@ __global__ __launch_bounds__(WGC* WGT * 64, 2) void rotate_quantize_kernel(
   }
 }
 
-template <int WGC, int WGT, int BK, int NBUF, bool PF = false>
+template <int WGC, int WGT, int BK>
 static int launch_cfg(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g, uint16_t* xh,
                       uint8_t* xl, uint16_t* sx, hipStream_t s, int m_off = 0, int sx_ld = 0) {
   // tokens [m_off, m_off + M) of the caller's arrays; sx_ld = total token count (row length of s_x)
@@ -256,7 +249,7 @@ static int launch_cfg(const uint16_t* x, const uint16_t* Qt, int M, int K, int r
   if (xh) xh += (size_t)m_off * r;
   if (xl) xl += (size_t)m_off * ((K - r) / 2);
   if (sx) sx += m_off;
-  using C = RQ<WGC, WGT, BK, NBUF>;
+  using C = RQ<WGC, WGT, BK>;
   const int r_pad = (r + 127) / 128 * 128;
   const int Kv = r_pad + (K - r + 127) / 128 * 128;
   const int n_ct = (Kv + C::TC - 1) / C::TC;
@@ -265,12 +258,12 @@ static int launch_cfg(const uint16_t* x, const uint16_t* Qt, int M, int K, int r
   const int per_xcd = (int)((n_blocks + 7) / 8);
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)rotate_quantize_kernel<WGC, WGT, BK, NBUF, PF>,
+    hipError_t e = hipFuncSetAttribute((const void*)rotate_quantize_kernel<WGC, WGT, BK>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
     if (e != hipSuccess) return hip_failed(e);
     attr_done = true;
   }
-  hipLaunchKernelGGL((rotate_quantize_kernel<WGC, WGT, BK, NBUF, PF>), dim3(per_xcd * 8), dim3(C::NT), C::SMEM, s, x,
+  hipLaunchKernelGGL((rotate_quantize_kernel<WGC, WGT, BK>), dim3(per_xcd * 8), dim3(C::NT), C::SMEM, s, x,
                      Qt, M, K, r, g, xh, xl, sx, r_pad, Kv, n_ct, n_tt, per_xcd, sx_ld);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? DIROTQ_OK : hip_failed(e);
@@ -285,25 +278,28 @@ int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, 
   const long n_tc256 = (Kv + 255) / 256;
   const long big_tiles = n_tc256 * ((M + 255) / 256);    // 256 channels x 256 tokens
   const long mid_tiles = n_tc256 * ((M + 127) / 128);    // 256 channels x 128 tokens
-#ifdef DIROTQ_RQ_FORCE   // build-time tuning aid: -DDIROTQ_RQ_FORCE=WGC,WGT,BK,NBUF[,PF]
+#ifdef DIROTQ_RQ_FORCE   // build-time tuning aid: -DDIROTQ_RQ_FORCE=WGC,WGT,BK
   return launch_cfg<DIROTQ_RQ_FORCE>(x, Qt, M, K, r, g, xh, xl, sx, s);
 #endif
-  if (K % 64 != 0) return launch_cfg<1, 2, 32, 4>(x, Qt, M, K, r, g, xh, xl, sx, s);
+  if (K % 64 != 0) {
+    if (mid_tiles >= 100) return launch_cfg<2, 2, 32>(x, Qt, M, K, r, g, xh, xl, sx, s);
+    return launch_cfg<1, 2, 32>(x, Qt, M, K, r, g, xh, xl, sx, s);
+  }
   if (big_tiles >= 200) {
-    // 256 CUs take one big tile each per round.  When the last round would be less than ~60%
+    // 256 CUs take one big tile each per round.  When the last round would be less than ~40%
     // full, the tokens of that round are done with half-size tiles in a second launch instead,
     // so that they spread over the whole chip.
     const long full = big_tiles / 256 * 256, tail = big_tiles - full;
     const int tt_big = (int)(full / n_tc256);               // token tiles covered by full rounds
-    if (full > 0 && tail > 0 && tail < 160 && tt_big * 256 < M && (M - tt_big * 256) % 128 == 0) {
-      int st = launch_cfg<2, 4, 64, 2, true>(x, Qt, tt_big * 256, K, r, g, xh, xl, sx, s, 0, M);
+    if (full > 0 && tail > 0 && tail <= 104 && tt_big * 256 < M && (M - tt_big * 256) % 128 == 0) {
+      int st = launch_cfg<2, 4, 64>(x, Qt, tt_big * 256, K, r, g, xh, xl, sx, s, 0, M);
       if (st) return st;
-      return launch_cfg<2, 2, 64, 2, true>(x, Qt, M - tt_big * 256, K, r, g, xh, xl, sx, s, tt_big * 256, M);
+      return launch_cfg<2, 2, 64>(x, Qt, M - tt_big * 256, K, r, g, xh, xl, sx, s, tt_big * 256, M);
     }
-    return launch_cfg<2, 4, 64, 2, true>(x, Qt, M, K, r, g, xh, xl, sx, s);
+    return launch_cfg<2, 4, 64>(x, Qt, M, K, r, g, xh, xl, sx, s);
   }
-  if (mid_tiles >= 100) return launch_cfg<2, 2, 64, 2>(x, Qt, M, K, r, g, xh, xl, sx, s);
-  return launch_cfg<1, 2, 64, 2>(x, Qt, M, K, r, g, xh, xl, sx, s);
+  if (mid_tiles >= 100) return launch_cfg<2, 2, 64>(x, Qt, M, K, r, g, xh, xl, sx, s);
+  return launch_cfg<1, 2, 32>(x, Qt, M, K, r, g, xh, xl, sx, s);
 }
 
 }  // namespace dirotq
