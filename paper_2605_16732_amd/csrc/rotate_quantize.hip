@@ -50,13 +50,12 @@ struct RQ {
   __device__ static __forceinline__ int swz(int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
 };
 
-template <int WGC, int WGT, int BK>
+template <int WGC, int WGT, int BK, int MI>
 __global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK>::WAVES_PER_SIMD)) void rotate_quantize_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ Qt, int M, int K, int r, int g,
     uint16_t* __restrict__ xh, uint8_t* __restrict__ xl, uint16_t* __restrict__ sx, int r_pad, int Kv, int n_ct,
     int n_tt, int per_xcd, int sx_ld) {
   using C = RQ<WGC, WGT, BK>;
-  constexpr int WT = 2;                                     // 32-token MFMA tiles per wave
   extern __shared__ __align__(16) unsigned char smem[];
 
   // consecutive workgroup ids go to different XCDs; give each XCD a contiguous run of tiles
@@ -100,147 +99,327 @@ __global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK>::WAVES_PER_SIMD)) 
     *(i32x4*)(smem + buf * C::STAGE_BYTES + (w * C::IPW + q) * 1024 + l * 16) = staged[q];
   };
 
-  f32x16 acc[4][WT];
-#pragma unroll
-  for (int i = 0; i < 4; i++)
-#pragma unroll
-    for (int j = 0; j < WT; j++)
-#pragma unroll
-      for (int v = 0; v < 16; v++) acc[i][j][v] = 0.0f;
+  const int nk = K / BK;                                    // the launcher guarantees K % BK == 0, nk >= 1
 
-  // operand read offsets (bytes within a stage) for k-step 0; k-step ks flips chunk bits
-  int offA[4], offB[WT];
-#pragma unroll
-  for (int i = 0; i < 4; i++) offA[i] = (wc * 128 + i * 32 + (l & 31)) * C::ROWB;
-#pragma unroll
-  for (int j = 0; j < WT; j++) offB[j] = (C::TC + wt * C::WAVE_T + j * 32 + (l & 31)) * C::ROWB;
-  const int swzA = C::swz(l & 31), swzB = C::swz(l & 31);   // tile bases are multiples of 32 rows
-
-  const int nk = K / BK;                                    // the launcher guarantees K % BK == 0
   // prologue: stage 0 into LDS, stage 1 into the registers.  Loads past the last stage re-read
   // it: unconditional loads keep the outstanding-load count the same in every iteration, so
   // the waits the compiler derives are exact.
 #pragma unroll
   for (int q = 0; q < C::IPW; q++) gload(q, 0);
 #pragma unroll
-  for (int q = 0; q < C::IPW; q++) {
-    swrite(q, 0);
-    gload(q, min(1, nk - 1));
-  }
+  for (int q = 0; q < C::IPW; q++) swrite(q, 0);
   __syncthreads();
-  bf16x8 a[2][4], b[2][WT];
-  for (int kt = 0; kt < nk; kt++) {
-    const unsigned char* sb = smem + (kt & 1) * C::STAGE_BYTES;
-    const int wbuf = (kt + 1) & 1, kt_load = min(kt + 2, nk - 1);
-    // operands of k-step ks+1 are fetched from LDS while the MFMAs of k-step ks run
-    auto lds_fetch = [&](int ks, int slot) {
-      const int chunk = 2 * ks + (l >> 5);
+  // the loads must be issued in the order the main loop consumes them: its waits count the loads
+  // issued after the one needed
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int i = 0; i < 4; i++) a[slot][i] = *(const bf16x8*)(sb + offA[i] + ((chunk ^ swzA) << 4));
-#pragma unroll
-      for (int j = 0; j < WT; j++) b[slot][j] = *(const bf16x8*)(sb + offB[j] + ((chunk ^ swzB) << 4));
-    };
-    lds_fetch(0, 0);
-#pragma unroll
-    for (int ks = 0; ks < C::KS; ks++) {
-      const int cur = ks & 1;
-      int pair = 0;
-#pragma unroll
-      for (int i = 0; i < 4; i++) {
-#pragma unroll
-        for (int j = 0; j < WT; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        if (i == 0 && ks + 1 < C::KS) lds_fetch(ks + 1, cur ^ 1);
-        // the PP store/load pairs of this k-step, spread over its four MFMA rows
-        if (pair < C::PP && i >= (pair * 4) / C::PP) {
-          const int q = ks * C::PP + pair;
-          swrite(q, wbuf);
-          gload(q, kt_load);
-          pair++;
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
-    __syncthreads();   // stage kt+1 is complete in LDS; stage kt may be overwritten
+  for (int q = 0; q < C::IPW; q++) {
+    gload(q, min(1, nk - 1));
+    __builtin_amdgcn_sched_barrier(0);
   }
 
-  // ---- epilogue, in registers ------------------------------------------------------
-  const int vb = ct * C::TC + wc * 128;                     // first virtual channel of this wave
-  if (vb >= Kv) return;
-  const int h = l >> 5;
-  if (vb < r_pad) {
-    // 16-bit part: 4 consecutive channels per register quad -> one 8-byte store
+  if constexpr (MI == 32) {
+    // ======== 32x32x16 MFMA: wave tile = 4 x 2 tiles of 32 channels x 32 tokens ========
+    constexpr int WT = 2;                                     // 32-token MFMA tiles per wave
+    f32x16 acc[4][WT];
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+#pragma unroll
+      for (int j = 0; j < WT; j++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) acc[i][j][v] = 0.0f;
+
+    // operand read offsets (bytes within a stage) for k-step 0; k-step ks flips chunk bits
+    int offA[4], offB[WT];
+#pragma unroll
+    for (int i = 0; i < 4; i++) offA[i] = (wc * 128 + i * 32 + (l & 31)) * C::ROWB;
+#pragma unroll
+    for (int j = 0; j < WT; j++) offB[j] = (C::TC + wt * C::WAVE_T + j * 32 + (l & 31)) * C::ROWB;
+    const int swzA = C::swz(l & 31), swzB = C::swz(l & 31);   // tile bases are multiples of 32 rows
+
+    bf16x8 a[2][4], b[2][WT];
+    int kt = 0;
+    do {                                                      // nk >= 1
+      const unsigned char* sb = smem + (kt & 1) * C::STAGE_BYTES;
+      const int wbuf = (kt + 1) & 1, kt_load = min(kt + 2, nk - 1);
+      // operands of k-step ks+1 are fetched from LDS while the MFMAs of k-step ks run
+      auto lds_fetch = [&](int ks, int slot) {
+        const int chunk = 2 * ks + (l >> 5);
+#pragma unroll
+        for (int i = 0; i < 4; i++) a[slot][i] = *(const bf16x8*)(sb + offA[i] + ((chunk ^ swzA) << 4));
+#pragma unroll
+        for (int j = 0; j < WT; j++) b[slot][j] = *(const bf16x8*)(sb + offB[j] + ((chunk ^ swzB) << 4));
+      };
+      lds_fetch(0, 0);
+#pragma unroll
+      for (int ks = 0; ks < C::KS; ks++) {
+        const int cur = ks & 1;
+        int pair = 0;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+#pragma unroll
+          for (int j = 0; j < WT; j++)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          if (i == 0 && ks + 1 < C::KS) lds_fetch(ks + 1, cur ^ 1);
+          // the PP store/load pairs of this k-step, spread over its four MFMA rows
+          if (pair < C::PP && i >= (pair * 4) / C::PP) {
+            const int q = ks * C::PP + pair;
+            swrite(q, wbuf);
+            gload(q, kt_load);
+            pair++;
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      __syncthreads();   // stage kt+1 is complete in LDS; stage kt may be overwritten
+    } while (++kt < nk);
+
+    // ---- epilogue, in registers ------------------------------------------------------
+    const int vb = ct * C::TC + wc * 128;                     // first virtual channel of this wave
+    if (vb >= Kv) return;
+    const int h = l >> 5;
+    if (vb < r_pad) {
+      // 16-bit part: 4 consecutive channels per register quad -> one 8-byte store
+#pragma unroll
+      for (int j = 0; j < WT; j++) {
+        const int m = m0 + wt * C::WAVE_T + j * 32 + (l & 31);
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+          for (int q = 0; q < 4; q++) {
+            const int c = vb + i * 32 + 8 * q + 4 * h;
+            if (c < r && m < M) {
+              uint2 o;
+              o.x = f32_to_bf16_bits(acc[i][j][4 * q]) | ((uint32_t)f32_to_bf16_bits(acc[i][j][4 * q + 1]) << 16);
+              o.y = f32_to_bf16_bits(acc[i][j][4 * q + 2]) | ((uint32_t)f32_to_bf16_bits(acc[i][j][4 * q + 3]) << 16);
+              *(uint2*)(xh + (size_t)m * r + c) = o;
+            }
+          }
+      }
+      return;
+    }
+    const int cl0 = vb - r_pad;                               // first 4-bit channel of this wave
+    const int KL = K - r;
+    const size_t xl_ld = (size_t)KL / 2;
+    const int gi_tiles = g >> 5;                              // 32-channel MFMA tiles per group: 1, 2, 4
 #pragma unroll
     for (int j = 0; j < WT; j++) {
       const int m = m0 + wt * C::WAVE_T + j * 32 + (l & 31);
+      // absmax of each 32-channel tile over the lane pair, then combined per group
+      float tmax[4];
 #pragma unroll
-      for (int i = 0; i < 4; i++)
+      for (int i = 0; i < 4; i++) {
+        float a = 0.0f;
+#pragma unroll
+        for (int v = 0; v < 16; v++) a = fmaxf(a, fabsf(acc[i][j][v]));
+        tmax[i] = fmaxf(a, __shfl_xor(a, 32));
+      }
+      if (gi_tiles == 2) {
+        tmax[0] = tmax[1] = fmaxf(tmax[0], tmax[1]);
+        tmax[2] = tmax[3] = fmaxf(tmax[2], tmax[3]);
+      } else if (gi_tiles == 4) {
+        tmax[0] = tmax[1] = tmax[2] = tmax[3] = fmaxf(fmaxf(tmax[0], tmax[1]), fmaxf(tmax[2], tmax[3]));
+      }
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        const int cl = cl0 + i * 32;                          // first 4-bit channel of this tile
+        const bool valid = cl < KL && m < M;
+        uint16_t sbits;
+        const float sf = group_scale(tmax[i], sbits);
+        const float inv = group_inv(sf);
+        if (valid && h == 0 && (i % gi_tiles) == 0) sx[(size_t)(cl / g) * sx_ld + m] = sbits;
+        // this lane's 16 codes: quad q covers channels cl + 8q + 4h .. +3 -> one 16-bit piece
+        uint32_t piece[4];
 #pragma unroll
         for (int q = 0; q < 4; q++) {
-          const int c = vb + i * 32 + 8 * q + 4 * h;
+          piece[q] = (uint32_t)(quant_code(acc[i][j][4 * q], inv) & 0xF) |
+                     (uint32_t)(quant_code(acc[i][j][4 * q + 1], inv) & 0xF) << 4 |
+                     (uint32_t)(quant_code(acc[i][j][4 * q + 2], inv) & 0xF) << 8 |
+                     (uint32_t)(quant_code(acc[i][j][4 * q + 3], inv) & 0xF) << 12;
+        }
+        const uint32_t P0 = piece[0] | (piece[1] << 16), P1 = piece[2] | (piece[3] << 16);
+        // lane h=0 keeps dwords 0,1 of the tile's 16 bytes, lane h=1 dwords 2,3
+        const uint32_t recv = __shfl_xor(h ? P0 : P1, 32);
+        const uint32_t lo = h ? recv : P0, hi = h ? P1 : recv;
+        uint2 o;
+        o.x = (lo & 0xFFFFu) | (hi << 16);
+        o.y = (lo >> 16) | (hi & 0xFFFF0000u);
+        if (valid) *(uint2*)(xl + (size_t)m * xl_ld + cl / 2 + 8 * h) = o;
+      }
+    }
+  } else {
+    // ======== 16x16x32 MFMA: wave tile = 8 x 4 tiles of 16 channels x 16 tokens =========
+    // Accumulator layout of a 16x16 tile: lane l holds channels 4*(l/16) .. +3 of token l%16, so
+    // the 16 channels of one token sit in the four lanes {t, t+16, t+32, t+48}; a quantization
+    // group (2, 4 or 8 tiles) is reduced in-lane and then across those four lanes.
+    constexpr int NI = 8, NJ = 4;                           // 16-channel x 16-token tiles per wave
+    constexpr int KS2 = BK / 32;                            // MFMA k-steps per stage
+    constexpr int PPS = C::IPW / KS2;                       // store/load pairs per k-step
+    static_assert(MI != 16 || (C::IPW % KS2 == 0 && PPS <= NI), "store/load pairs are spread over the 8 tile rows of a k-step");
+    f32x4 acc[NI][NJ];
+#pragma unroll
+    for (int i = 0; i < NI; i++)
+#pragma unroll
+      for (int j = 0; j < NJ; j++)
+#pragma unroll
+        for (int v = 0; v < 4; v++) acc[i][j][v] = 0.0f;
+
+    // operand reads: lane l takes row l%16 of a tile, 16-byte chunk 4*ks + l/16 of the stage's k range
+    const int lr = l & 15, hq = l >> 4;
+    const int offA = (wc * 128 + lr) * C::ROWB, offB = (C::TC + wt * 64 + lr) * C::ROWB;
+    const int sw = C::swz(lr);                                // tile bases are multiples of 16 rows
+
+    bf16x8 a[3], b[2][NJ];
+    int kt = 0;
+    do {                                                      // nk >= 1
+      const unsigned char* sb = smem + (kt & 1) * C::STAGE_BYTES;
+      const int wbuf = (kt + 1) & 1, kt_load = min(kt + 2, nk - 1);
+      // flat index f = ks*NI + i over the stage's (k-step, channel tile) pairs; A tiles are fetched two
+      // ahead of their MFMAs, the B tiles of the next k-step during the current one
+      auto fetch_a = [&](int f) {
+        const int ks = f / NI, i = f % NI;
+        a[f % 3] = *(const bf16x8*)(sb + offA + i * 16 * C::ROWB + (((4 * ks + hq) ^ sw) << 4));
+      };
+      auto fetch_b = [&](int ks, int j) {
+        b[ks & 1][j] = *(const bf16x8*)(sb + offB + j * 16 * C::ROWB + (((4 * ks + hq) ^ sw) << 4));
+      };
+#pragma unroll
+      for (int j = 0; j < NJ; j++) fetch_b(0, j);
+      fetch_a(0);
+      fetch_a(1);
+#pragma unroll
+      for (int f = 0; f < KS2 * NI; f++) {
+        const int ks = f / NI, i = f % NI;
+        if (f + 2 < KS2 * NI) fetch_a(f + 2);
+        if (ks + 1 < KS2 && i >= 2 && i < 2 + NJ) fetch_b(ks + 1, i - 2);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < NJ; j++)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[f % 3], b[ks & 1][j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        // the PPS store/load pairs of this k-step, spread over its tile rows
+#pragma unroll
+        for (int p = 0; p < PPS; p++)
+          if (i == (p * NI) / PPS) {
+            const int q = ks * PPS + p;
+            swrite(q, wbuf);
+            gload(q, kt_load);
+          }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      __syncthreads();   // stage kt+1 is complete in LDS; stage kt may be overwritten
+    } while (++kt < nk);
+
+    // ---- epilogue, in registers ------------------------------------------------------
+    const int vb = ct * C::TC + wc * 128;                     // first virtual channel of this wave
+    if (vb >= Kv) return;
+    if (vb < r_pad) {
+      // 16-bit part: the lane's 4 consecutive channels of a tile -> one 8-byte store
+#pragma unroll
+      for (int j = 0; j < NJ; j++) {
+        const int m = m0 + wt * 64 + j * 16 + lr;
+#pragma unroll
+        for (int i = 0; i < NI; i++) {
+          const int c = vb + i * 16 + 4 * hq;
           if (c < r && m < M) {
             uint2 o;
-            o.x = f32_to_bf16_bits(acc[i][j][4 * q]) | ((uint32_t)f32_to_bf16_bits(acc[i][j][4 * q + 1]) << 16);
-            o.y = f32_to_bf16_bits(acc[i][j][4 * q + 2]) | ((uint32_t)f32_to_bf16_bits(acc[i][j][4 * q + 3]) << 16);
+            o.x = f32_to_bf16_bits(acc[i][j][0]) | ((uint32_t)f32_to_bf16_bits(acc[i][j][1]) << 16);
+            o.y = f32_to_bf16_bits(acc[i][j][2]) | ((uint32_t)f32_to_bf16_bits(acc[i][j][3]) << 16);
             *(uint2*)(xh + (size_t)m * r + c) = o;
           }
         }
-    }
-    return;
-  }
-  const int cl0 = vb - r_pad;                               // first 4-bit channel of this wave
-  const int KL = K - r;
-  const size_t xl_ld = (size_t)KL / 2;
-  const int gi_tiles = g >> 5;                              // 32-channel MFMA tiles per group: 1, 2, 4
-#pragma unroll
-  for (int j = 0; j < WT; j++) {
-    const int m = m0 + wt * C::WAVE_T + j * 32 + (l & 31);
-    // absmax of each 32-channel tile over the lane pair, then combined per group
-    float tmax[4];
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-      float a = 0.0f;
-#pragma unroll
-      for (int v = 0; v < 16; v++) a = fmaxf(a, fabsf(acc[i][j][v]));
-      tmax[i] = fmaxf(a, __shfl_xor(a, 32));
-    }
-    if (gi_tiles == 2) {
-      tmax[0] = tmax[1] = fmaxf(tmax[0], tmax[1]);
-      tmax[2] = tmax[3] = fmaxf(tmax[2], tmax[3]);
-    } else if (gi_tiles == 4) {
-      tmax[0] = tmax[1] = tmax[2] = tmax[3] = fmaxf(fmaxf(tmax[0], tmax[1]), fmaxf(tmax[2], tmax[3]));
-    }
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-      const int cl = cl0 + i * 32;                          // first 4-bit channel of this tile
-      const bool valid = cl < KL && m < M;
-      uint16_t sbits;
-      const float sf = group_scale(tmax[i], sbits);
-      const float inv = group_inv(sf);
-      if (valid && h == 0 && (i % gi_tiles) == 0) sx[(size_t)(cl / g) * sx_ld + m] = sbits;
-      // this lane's 16 codes: quad q covers channels cl + 8q + 4h .. +3 -> one 16-bit piece
-      uint32_t piece[4];
-#pragma unroll
-      for (int q = 0; q < 4; q++) {
-        piece[q] = (uint32_t)(quant_code(acc[i][j][4 * q], inv) & 0xF) |
-                   (uint32_t)(quant_code(acc[i][j][4 * q + 1], inv) & 0xF) << 4 |
-                   (uint32_t)(quant_code(acc[i][j][4 * q + 2], inv) & 0xF) << 8 |
-                   (uint32_t)(quant_code(acc[i][j][4 * q + 3], inv) & 0xF) << 12;
       }
-      const uint32_t P0 = piece[0] | (piece[1] << 16), P1 = piece[2] | (piece[3] << 16);
-      // lane h=0 keeps dwords 0,1 of the tile's 16 bytes, lane h=1 dwords 2,3
-      const uint32_t recv = __shfl_xor(h ? P0 : P1, 32);
-      const uint32_t lo = h ? recv : P0, hi = h ? P1 : recv;
-      uint2 o;
-      o.x = (lo & 0xFFFFu) | (hi << 16);
-      o.y = (lo >> 16) | (hi & 0xFFFF0000u);
-      if (valid) *(uint2*)(xl + (size_t)m * xl_ld + cl / 2 + 8 * h) = o;
+      return;
+    }
+    const int cl0 = vb - r_pad;                               // first 4-bit channel of this wave
+    const int KL = K - r;
+    const size_t xl_ld = (size_t)KL / 2;
+    const int gu = g >> 5;                                    // 32-channel units per group: 1, 2, 4
+    // The four lanes of a token are the four 16-lane rows of the wave; data moves between them with
+    // the row-swap instructions of gfx950 (4 swaps transpose a 4x4 block of dwords over rows x registers).
+    auto swap16 = [](uint32_t& x, uint32_t& y) {              // rows (x1 <-> y0), (x3 <-> y2)
+      auto v = __builtin_amdgcn_permlane16_swap(x, y, false, false);
+      x = v[0];
+      y = v[1];
+    };
+    auto swap32 = [](uint32_t& x, uint32_t& y) {              // rows (x2 <-> y0), (x3 <-> y1)
+      auto v = __builtin_amdgcn_permlane32_swap(x, y, false, false);
+      x = v[0];
+      y = v[1];
+    };
+    auto transpose4 = [&](uint32_t (&v)[4]) {                 // afterwards v[h] on row q = old v[q] on row h
+      swap16(v[0], v[1]);
+      swap16(v[2], v[3]);
+      swap32(v[0], v[2]);
+      swap32(v[1], v[3]);
+    };
+#pragma unroll
+    for (int j = 0; j < NJ; j++) {
+      const int m = m0 + wt * 64 + j * 16 + lr;
+      // absmax per 32-channel unit (two tiles) in-lane; after the transpose row q holds unit q's
+      // four partial maxima, so row q finishes unit q
+      uint32_t um[4];
+#pragma unroll
+      for (int u = 0; u < 4; u++) {
+        float v = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 4; e++) v = fmaxf(v, fmaxf(fabsf(acc[2 * u][j][e]), fabsf(acc[2 * u + 1][j][e])));
+        um[u] = __builtin_bit_cast(uint32_t, v);
+      }
+      transpose4(um);
+      float gm = fmaxf(fmaxf(__builtin_bit_cast(float, um[0]), __builtin_bit_cast(float, um[1])),
+                       fmaxf(__builtin_bit_cast(float, um[2]), __builtin_bit_cast(float, um[3])));
+      if (gu > 1) {                                           // groups of 2 or 4 units: combine rows
+        uint32_t e0 = __builtin_bit_cast(uint32_t, gm), e1 = e0;
+        swap16(e0, e1);                                       // e0 = rows (0,0,2,2), e1 = rows (1,1,3,3)
+        gm = fmaxf(__builtin_bit_cast(float, e0), __builtin_bit_cast(float, e1));
+        if (gu > 2) {
+          uint32_t f0 = __builtin_bit_cast(uint32_t, gm), f1 = f0;
+          swap32(f0, f1);                                     // f0 = rows (0,1,0,1), f1 = rows (2,3,2,3)
+          gm = fmaxf(__builtin_bit_cast(float, f0), __builtin_bit_cast(float, f1));
+        }
+      }
+      // row q: scale of the group that unit q belongs to
+      uint16_t sbits;
+      const float sf = group_scale(gm, sbits);
+      const float inv_q = group_inv(sf);
+      const int clu = cl0 + 32 * hq;                          // first channel of unit hq
+      const bool valid = clu < KL && m < M;
+      if (valid && (hq % gu) == 0) sx[(size_t)(clu / g) * sx_ld + m] = sbits;
+      // broadcast the four reciprocals to all rows
+      uint32_t i0 = __builtin_bit_cast(uint32_t, inv_q), i1 = i0;
+      swap16(i0, i1);                                         // i0 = rows (0,0,2,2), i1 = rows (1,1,3,3)
+      uint32_t i2 = i0, i3 = i1;
+      swap32(i0, i2);                                         // i0 = row 0 everywhere, i2 = row 2 everywhere
+      swap32(i1, i3);                                         // i1 = row 1 everywhere, i3 = row 3 everywhere
+      const float inv[4] = {__builtin_bit_cast(float, i0), __builtin_bit_cast(float, i1),
+                            __builtin_bit_cast(float, i2), __builtin_bit_cast(float, i3)};
+      // codes: P[u] = the lane's 4 + 4 codes of unit u (tile 2u in the low half, tile 2u+1 in the high half)
+      uint32_t P[4];
+#pragma unroll
+      for (int u = 0; u < 4; u++) {
+        uint32_t pc = 0;
+#pragma unroll
+        for (int half = 0; half < 2; half++)
+#pragma unroll
+          for (int e = 0; e < 4; e++)
+            pc |= (uint32_t)(quant_code(acc[2 * u + half][j][e], inv[u]) & 0xF) << (16 * half + 4 * e);
+        P[u] = pc;
+      }
+      transpose4(P);                                          // P[h] = row h's codes of unit hq
+      // unit hq = 16 bytes: tile 2hq (low halves, rows 0..3 in channel order), then tile 2hq+1
+      uint4 o;
+      o.x = (P[0] & 0xFFFFu) | (P[1] << 16);
+      o.y = (P[2] & 0xFFFFu) | (P[3] << 16);
+      o.z = (P[0] >> 16) | (P[1] & 0xFFFF0000u);
+      o.w = (P[2] >> 16) | (P[3] & 0xFFFF0000u);
+      if (valid) *(uint4*)(xl + (size_t)m * xl_ld + clu / 2) = o;
     }
   }
 }
 
-template <int WGC, int WGT, int BK>
+template <int WGC, int WGT, int BK, int MI>
 static int launch_cfg(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g, uint16_t* xh,
                       uint8_t* xl, uint16_t* sx, hipStream_t s, int m_off = 0, int sx_ld = 0) {
   // tokens [m_off, m_off + M) of the caller's arrays; sx_ld = total token count (row length of s_x)
@@ -258,12 +437,12 @@ static int launch_cfg(const uint16_t* x, const uint16_t* Qt, int M, int K, int r
   const int per_xcd = (int)((n_blocks + 7) / 8);
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)rotate_quantize_kernel<WGC, WGT, BK>,
+    hipError_t e = hipFuncSetAttribute((const void*)rotate_quantize_kernel<WGC, WGT, BK, MI>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
     if (e != hipSuccess) return hip_failed(e);
     attr_done = true;
   }
-  hipLaunchKernelGGL((rotate_quantize_kernel<WGC, WGT, BK>), dim3(per_xcd * 8), dim3(C::NT), C::SMEM, s, x,
+  hipLaunchKernelGGL((rotate_quantize_kernel<WGC, WGT, BK, MI>), dim3(per_xcd * 8), dim3(C::NT), C::SMEM, s, x,
                      Qt, M, K, r, g, xh, xl, sx, r_pad, Kv, n_ct, n_tt, per_xcd, sx_ld);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? DIROTQ_OK : hip_failed(e);
@@ -273,17 +452,21 @@ int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, 
                            uint8_t* xl, uint16_t* sx, hipStream_t s) {
   // Large problems: 256 x 256 workgroup tiles (8 waves); medium: 256 channels x 128 tokens
   // (4 waves); small: 128 x 128 (2 waves), so that the grid still covers the chip.
+  // The large tiles run long enough to be limited by power (the shader clock drops under
+  // sustained MFMA work on random data); there the 16x16x32 MFMA, which moves half the
+  // accumulator bytes per multiply-add, is the faster one.  The smaller, latency-bound
+  // launches are faster with the 32x32x16 MFMA and its shorter epilogue.
   const int r_pad = (r + 127) / 128 * 128;
   const int Kv = r_pad + (K - r + 127) / 128 * 128;
   const long n_tc256 = (Kv + 255) / 256;
   const long big_tiles = n_tc256 * ((M + 255) / 256);    // 256 channels x 256 tokens
   const long mid_tiles = n_tc256 * ((M + 127) / 128);    // 256 channels x 128 tokens
-#ifdef DIROTQ_RQ_FORCE   // build-time tuning aid: -DDIROTQ_RQ_FORCE=WGC,WGT,BK
+#ifdef DIROTQ_RQ_FORCE   // build-time tuning aid: -DDIROTQ_RQ_FORCE=WGC,WGT,BK,MI (K % BK must be 0)
   return launch_cfg<DIROTQ_RQ_FORCE>(x, Qt, M, K, r, g, xh, xl, sx, s);
 #endif
   if (K % 64 != 0) {
-    if (mid_tiles >= 100) return launch_cfg<2, 2, 32>(x, Qt, M, K, r, g, xh, xl, sx, s);
-    return launch_cfg<1, 2, 32>(x, Qt, M, K, r, g, xh, xl, sx, s);
+    if (mid_tiles >= 100) return launch_cfg<2, 2, 32, 32>(x, Qt, M, K, r, g, xh, xl, sx, s);
+    return launch_cfg<1, 2, 32, 32>(x, Qt, M, K, r, g, xh, xl, sx, s);
   }
   if (big_tiles >= 200) {
     // 256 CUs take one big tile each per round.  When the last round would be less than ~40%
@@ -292,14 +475,14 @@ int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, 
     const long full = big_tiles / 256 * 256, tail = big_tiles - full;
     const int tt_big = (int)(full / n_tc256);               // token tiles covered by full rounds
     if (full > 0 && tail > 0 && tail <= 104 && tt_big * 256 < M && (M - tt_big * 256) % 128 == 0) {
-      int st = launch_cfg<2, 4, 64>(x, Qt, tt_big * 256, K, r, g, xh, xl, sx, s, 0, M);
+      int st = launch_cfg<2, 4, 64, 16>(x, Qt, tt_big * 256, K, r, g, xh, xl, sx, s, 0, M);
       if (st) return st;
-      return launch_cfg<2, 2, 64>(x, Qt, M - tt_big * 256, K, r, g, xh, xl, sx, s, tt_big * 256, M);
+      return launch_cfg<2, 2, 64, 32>(x, Qt, M - tt_big * 256, K, r, g, xh, xl, sx, s, tt_big * 256, M);
     }
-    return launch_cfg<2, 4, 64>(x, Qt, M, K, r, g, xh, xl, sx, s);
+    return launch_cfg<2, 4, 64, 16>(x, Qt, M, K, r, g, xh, xl, sx, s);
   }
-  if (mid_tiles >= 100) return launch_cfg<2, 2, 64>(x, Qt, M, K, r, g, xh, xl, sx, s);
-  return launch_cfg<1, 2, 32>(x, Qt, M, K, r, g, xh, xl, sx, s);
+  if (mid_tiles >= 100) return launch_cfg<2, 2, 64, 32>(x, Qt, M, K, r, g, xh, xl, sx, s);
+  return launch_cfg<1, 2, 32, 32>(x, Qt, M, K, r, g, xh, xl, sx, s);
 }
 
 }  // namespace dirotq
