@@ -33,7 +33,8 @@
  *  - Supported shapes: M >= 0 (M == 0 is a no-op), N >= 1, K a multiple of 32,
  *    0 <= r <= K with r a multiple of 32, g in {32, 64, 128}, (K - r) % g == 0.
  *  - INT4 packing (activations): byte i of a row holds channel 2i of the 4-bit part
- *    in bits 0-3 and channel 2i+1 in bits 4-7, two's-complement nibbles.
+ *    in bits 0-3 and channel 2i+1 in bits 4-7.  A nibble is the code q in [-7, 7] in
+ *    sign-magnitude form: bit 3 = sign, bits 0-2 = |q|; zero is always 0x0.
  *  - Activation scales are group-major: s_x[j * M + m] for group j, token m.
  */
 #ifndef DIROTQ_H

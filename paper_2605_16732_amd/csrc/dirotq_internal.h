@@ -104,6 +104,12 @@ __device__ __forceinline__ int quant_code(float v, float inv) {
   t = fminf(fmaxf(t, -7.0f), 7.0f);
   return (int)t;
 }
+// Stored form of a code q in [-7, 7]: sign-magnitude nibble, bit 3 = sign, bits 0-2 = |q|
+// (zero is always 0x0).  Zero-extended to a byte with the sign moved to bit 7 this is the
+// fp8 (E4M3) number q * 2^-9, which is how the GEMM kernel feeds codes to the matrix pipe.
+__device__ __forceinline__ uint32_t code_nibble(int q) { return (uint32_t)(q < 0 ? (8 - q) : q) & 15u; }
+__device__ __forceinline__ uint32_t quant_nibble(float v, float inv) { return code_nibble(quant_code(v, inv)); }
+__device__ __forceinline__ int nibble_code(uint32_t nib) { return (nib & 8u) ? -(int)(nib & 7u) : (int)(nib & 7u); }
 #endif
 
 }  // namespace dirotq

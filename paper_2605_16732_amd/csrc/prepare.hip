@@ -106,7 +106,7 @@ __global__ __launch_bounds__(256) void split_quantize_rows_kernel(const float* _
   scales[(size_t)j * rows + row] = sbits;
   uint8_t* d = codes + (size_t)row * ((K - r) / 2) + j * (g / 2);
   for (int p = 0; p < g; p += 2)
-    d[p / 2] = (uint8_t)((quant_code(s[p], inv) & 0xF) | ((quant_code(s[p + 1], inv) & 0xF) << 4));
+    d[p / 2] = (uint8_t)(quant_nibble(s[p], inv) | (quant_nibble(s[p + 1], inv) << 4));
 }
 
 int launch_prepare_weights(const float* W, const float* Q, int N, int K, int r, int g, void* blob,
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(256) void import_kernel(const uint16_t* __restrict_
   const long n_wh = (long)N * r, n_q = (long)N * (K - r) / 2;
   const int G = (K - r) / g;
   if (i < n_wh) bwh[i] = Wh[i];
-  if (i < n_q) bq[i] = (uint8_t)((codes[2 * i] & 0xF) | ((codes[2 * i + 1] & 0xF) << 4));
+  if (i < n_q) bq[i] = (uint8_t)(code_nibble(codes[2 * i]) | (code_nibble(codes[2 * i + 1]) << 4));
   if (i < (long)N * G) {
     const int n = (int)(i / G), j = (int)(i % G);
     bsw[(size_t)j * N + n] = sw[i];
@@ -151,8 +151,8 @@ __global__ __launch_bounds__(256) void export_kernel(const uint16_t* __restrict_
   if (Wh && i < n_wh) Wh[i] = bwh[i];
   if (codes && i < n_q) {
     const int b = bq[i];
-    codes[2 * i] = (int8_t)(((int)((uint32_t)b << 28)) >> 28);       // sign-extend bits 0-3
-    codes[2 * i + 1] = (int8_t)(((int)((uint32_t)b << 24)) >> 28);   // sign-extend bits 4-7
+    codes[2 * i] = (int8_t)nibble_code(b & 15);
+    codes[2 * i + 1] = (int8_t)nibble_code(b >> 4);
   }
   if (sw && i < (long)N * G) {
     const int n = (int)(i / G), j = (int)(i % G);

@@ -233,10 +233,10 @@ __global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK>::WAVES_PER_SIMD)) 
         uint32_t piece[4];
 #pragma unroll
         for (int q = 0; q < 4; q++) {
-          piece[q] = (uint32_t)(quant_code(acc[i][j][4 * q], inv) & 0xF) |
-                     (uint32_t)(quant_code(acc[i][j][4 * q + 1], inv) & 0xF) << 4 |
-                     (uint32_t)(quant_code(acc[i][j][4 * q + 2], inv) & 0xF) << 8 |
-                     (uint32_t)(quant_code(acc[i][j][4 * q + 3], inv) & 0xF) << 12;
+          piece[q] = quant_nibble(acc[i][j][4 * q], inv) |
+                     quant_nibble(acc[i][j][4 * q + 1], inv) << 4 |
+                     quant_nibble(acc[i][j][4 * q + 2], inv) << 8 |
+                     quant_nibble(acc[i][j][4 * q + 3], inv) << 12;
         }
         const uint32_t P0 = piece[0] | (piece[1] << 16), P1 = piece[2] | (piece[3] << 16);
         // lane h=0 keeps dwords 0,1 of the tile's 16 bytes, lane h=1 dwords 2,3
@@ -404,7 +404,7 @@ __global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK>::WAVES_PER_SIMD)) 
         for (int half = 0; half < 2; half++)
 #pragma unroll
           for (int e = 0; e < 4; e++)
-            pc |= (uint32_t)(quant_code(acc[2 * u + half][j][e], inv[u]) & 0xF) << (16 * half + 4 * e);
+            pc |= quant_nibble(acc[2 * u + half][j][e], inv[u]) << (16 * half + 4 * e);
         P[u] = pc;
       }
       transpose4(P);                                          // P[h] = row h's codes of unit hq

@@ -7,33 +7,36 @@
 // (tokens), each 64 n x 64 tokens = 2 x 2 MFMA tiles; two workgroups share a CU so that
 // one's barrier / staging phase overlaps the other's arithmetic.
 //
-// Integer part.  INT4 codes are unpacked once per workgroup on their way into LDS: a
-// nibble is moved to the high half of a byte, so the i8 MFMA operand holds 16 q and the
-// int32 group dot is 256 I exactly (|256 I| <= 256 * 49 * 128 < 2^31).  Even and odd
-// channels of an 8-channel dword land in different operand registers; both operands use
-// the same permutation, so the dot product is unchanged.
+// Integer part.  A stored code is a sign-magnitude nibble.  On its way into LDS (once per
+// workgroup) it becomes the byte [sign 0000 magnitude], which read as fp8 (E4M3) is the
+// subnormal q * 2^-9: the fp8 matrix pipe then multiplies and adds the codes exactly
+// (products and sums of small integers times 2^-18, far inside fp32) and hands back the
+// group dot as a float, so no integer-to-float conversion is left for the vector ALU.
+// Even and odd channels of an 8-channel dword land in different operand registers; both
+// operands use the same permutation, so the dot product is unchanged.  One 32x32x64 MFMA
+// covers a 64-channel group (two for 128, a half-empty one for 32).
 //
 // Dequantisation.  The per-group scale product P[n][token] = s_w[n,j] * s_x[token,j] is an
 // outer product of fp16 vectors: it is produced exactly (fp16 x fp16 fits fp32) by one
 // fp16 MFMA whose operands carry the scales in k-slot 0 and zeros elsewhere, which
-// leaves the vector ALU one convert and one fma per accumulator and group:
-// acc += float(256 I) * P.  The common factor 2^-8 is applied once at the end (exact),
-// before the 16-bit branch is accumulated on top by bf16 MFMAs.
+// leaves the vector ALU one fma per accumulator and group: acc += (2^-18 I) * P.  The
+// common factor 2^18 is applied once at the end (exact), before the 16-bit branch is
+// accumulated on top by bf16 MFMAs.
 //
-// Schedule.  The vector ALU is the binding unit (2 ops per accumulator and group against
-// 64 cycles of i8 MFMA per tile and group), so the main loop is software-pipelined by
-// hand: the MFMAs of tile s+1 are issued before the convert/fma sweep of tile s, and the
-// LDS operand reads of the next group are issued one sweep ahead.
+// Schedule.  The vector ALU is the binding unit (one fma per accumulator and group plus the
+// unpacking, against 64 cycles of fp8 MFMA per tile and 64-channel group), so the main loop
+// is software-pipelined by hand: the MFMAs of tile s+1 are issued before the fma sweep of
+// tile s, and the LDS operand reads of the next group are issued one sweep ahead.
 #include "dirotq_internal.h"
 
 namespace dirotq {
 
 constexpr int TN = 128;         // output channels per workgroup tile
 constexpr int TM = 128;         // tokens per workgroup tile
-constexpr int BKQ = 128;        // 4-bit channels per LDS stage (one 128-byte i8 row)
+constexpr int BKQ = 128;        // 4-bit channels per LDS stage (one 128-byte fp8 row)
 constexpr int NTHREADS = 256;   // 4 waves as 2 (n) x 2 (tokens), 64 n x 64 tokens each
 constexpr int ROWS = TN + TM;
-constexpr int STAGE_BYTES = ROWS * 128;              // i8 [256 rows][128 B] (= bf16 [256][64])
+constexpr int STAGE_BYTES = ROWS * 128;              // fp8 [256 rows][128 B] (= bf16 [256][64])
 constexpr int SCALE_OFF = 2 * STAGE_BYTES;           // u64 [2 bufs][4 groups][256 rows]: {fp16 scale, 0, 0, 0}
 // per buffer: (groups per stage) x ROWS x 8 bytes, then 8 zero bytes read by lanes 32..63
 constexpr int scale_buf_bytes(int gs) { return (BKQ / gs) * ROWS * 8; }
@@ -47,10 +50,19 @@ __device__ __forceinline__ int tile_off_bytes(int row, int chunk) {
   return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
 }
 
-// 8 nibbles of a dword -> two dwords of i8 holding 16*q: even channels, odd channels
+// 8 sign-magnitude nibbles of a dword -> two dwords of fp8 (E4M3) bytes [s 0000 mmm], i.e. the
+// values +-m * 2^-9 (subnormals, exact): even channels, odd channels
 __device__ __forceinline__ void unpack8(uint32_t p, uint32_t& even, uint32_t& odd) {
-  even = (p << 4) & 0xF0F0F0F0u;
-  odd = p & 0xF0F0F0F0u;
+  even = (p & 0x07070707u) | ((p & 0x08080808u) << 4);
+  odd = ((p >> 4) & 0x07070707u) | (p & 0x80808080u);
+}
+
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+// one 32x32x64 fp8 MFMA step (no block scaling)
+__device__ __forceinline__ f32x16 mfma_fp8_k64(i32x4 a_lo, i32x4 a_hi, i32x4 b_lo, i32x4 b_hi, f32x16 c) {
+  const i32x8 a = __builtin_shufflevector(a_lo, a_hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  const i32x8 b = __builtin_shufflevector(b_lo, b_hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);
 }
 
 template <int GS, bool OUT_F32>
@@ -76,7 +88,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
   const int KL = K - r;            // number of 4-bit channels
   const int G = KL / GS;
   constexpr int GPS = BKQ / GS;    // groups per stage
-  constexpr int MPG = GS / 32;     // i8 MFMAs (k = 32) per group
+  constexpr int MPG = GS / 32;     // 16-byte operand chunks (32 channels over the lane pair) per group
   constexpr int SCALE_BUF_BYTES = scale_buf_bytes(GS), ZERO_OFF = zero_off(GS);
 
   if (t < 64) ((uint32_t*)(smem + ZERO_OFF))[t] = 0u;   // read as the zero operand half
@@ -188,7 +200,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
       const int st2 = min(st + 2, nst - 1);     // past the end: harmless re-load, never used
       const unsigned char* sb = smem + buf * STAGE_BYTES;
       const unsigned char* ssb = smem + buf * sbufstep;
-      // operands of one group: i8 codes of 2 weight tiles and 2 token tiles, and their scales
+      // operands of one group: fp8 codes of 2 weight tiles and 2 token tiles, and their scales
       i32x4 a[2][MPG], b[2][MPG];
       f16x4 sa[2], sbv[2];
       auto load_ops = [&](int jj) {
@@ -204,26 +216,23 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
 #pragma unroll
         for (int j = 0; j < 2; j++) sbv[j] = *(const f16x4*)(ssb + soffB[j] + jj * sstep);
       };
-      i32x16 I[2];
-      f32x16 P[2];
-      auto issue = [&](int i, int j, int slot) {     // 256 I and the scale product of tile (i, j)
-        // the scale-product MFMA sits between the first two (dependent) integer MFMAs, so the
-        // second one finds its accumulator ready instead of stalling the wave at issue
-        i32x16 z;
+      f32x16 I[2], P[2];
+      auto issue = [&](int i, int j, int slot) {     // 2^-18 I and the scale product of tile (i, j)
+        // (for 128-channel groups the scale-product MFMA sits between the two dependent code
+        // MFMAs, so the second one finds its accumulator ready instead of stalling the wave)
+        const i32x4 zero4 = {0, 0, 0, 0};
+        f32x16 z, p;
 #pragma unroll
-        for (int v = 0; v < 16; v++) z[v] = 0;
-        z = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i][0], b[j][0], z, 0, 0, 0);
-        f32x16 p;
-#pragma unroll
-        for (int v = 0; v < 16; v++) p[v] = 0.0f;
+        for (int v = 0; v < 16; v++) z[v] = p[v] = 0.0f;
+        if (MPG == 1) z = mfma_fp8_k64(a[i][0], zero4, b[j][0], zero4, z);     // 32 channels: upper k half empty
+        else z = mfma_fp8_k64(a[i][0], a[i][1], b[j][0], b[j][1], z);
         P[slot] = __builtin_amdgcn_mfma_f32_32x32x8f16(sa[i], sbv[j], p, 0, 0, 0);
-#pragma unroll
-        for (int kk = 1; kk < MPG; kk++) z = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i][kk], b[j][kk], z, 0, 0, 0);
+        if (MPG == 4) z = mfma_fp8_k64(a[i][2], a[i][3], b[j][2], b[j][3], z);
         I[slot] = z;
       };
-      auto sweep = [&](int i, int j, int slot) {     // acc += float(256 I) * P for tile (i, j)
+      auto sweep = [&](int i, int j, int slot) {     // acc += (2^-18 I) * P for tile (i, j)
 #pragma unroll
-        for (int v = 0; v < 16; v++) acc[i][j][v] = fmaf((float)I[slot][v], P[slot][v], acc[i][j][v]);
+        for (int v = 0; v < 16; v++) acc[i][j][v] = fmaf(I[slot][v], P[slot][v], acc[i][j][v]);
         asm volatile("" : "+v"(acc[i][j]));            // pin the sweep here (keeps I/P live ranges short)
       };
       // the next stage's unpack work is spread over the last four tile sweeps of this stage
@@ -239,11 +248,11 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
           }
         }
       };
-      // One pipeline step = the MFMAs of the next tile interleaved with the convert/fma sweep of
+      // One pipeline step = the MFMAs of the next tile interleaved with the fma sweep of
       // the current one (so that neither the matrix pipe nor the vector ALU waits for the other
       // inside a wave): 1 MFMA, then a share of the VALU work, repeated.
       auto interleave = [&](bool valu_first) {
-        constexpr int NM = MPG + 1, PER = 32 / NM;
+        constexpr int NM = (MPG == 4 ? 2 : 1) + 1, PER = 16 / NM;
         if (valu_first) __builtin_amdgcn_sched_group_barrier(0x002, PER, 0);
 #pragma unroll
         for (int q = 0; q < NM; q++) {
@@ -282,13 +291,13 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
       }
       __syncthreads();
     }
-    // undo the two 16x operand factors (exact power of two)
+    // undo the two 2^-9 operand factors (exact power of two)
 #pragma unroll
     for (int i = 0; i < 2; i++)
 #pragma unroll
       for (int j = 0; j < 2; j++)
 #pragma unroll
-        for (int v = 0; v < 16; v++) acc[i][j][v] *= 0.00390625f;
+        for (int v = 0; v < 16; v++) acc[i][j][v] *= 262144.0f;
   }
 
   // ---- 16-bit branch: acc += W'_h x_h^T, bf16 MFMA, 64 channels per pass ----------

@@ -32,6 +32,24 @@ def dev(a: np.ndarray) -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
 
 
+def pack_codes(q: np.ndarray) -> np.ndarray:
+    """int codes in [-7, 7], shape [rows, C] -> the library's packed form [rows, C/2]: two
+    sign-magnitude nibbles per byte (bit 3 = sign, bits 0-2 = |q|), even channel low."""
+    q = np.asarray(q).astype(np.int16)
+    assert q.min() >= -7 and q.max() <= 7 and q.shape[-1] % 2 == 0
+    nib = (np.abs(q) | np.where(q < 0, 8, 0)).astype(np.uint8)
+    return np.ascontiguousarray(nib[..., 0::2] | (nib[..., 1::2] << 4))
+
+
+def unpack_codes(b: np.ndarray) -> np.ndarray:
+    """Inverse of pack_codes -> int8 codes [rows, C]; a stored "minus zero" (0x8) is rejected."""
+    b = np.asarray(b, dtype=np.uint8)
+    nib = np.stack([b & 15, b >> 4], axis=-1).reshape(*b.shape[:-1], b.shape[-1] * 2)
+    assert not np.any(nib == 8), "sign bit set on a zero code"
+    mag = (nib & 7).astype(np.int8)
+    return np.where(nib & 8, -mag, mag).astype(np.int8)
+
+
 def import_blob(Wh, qw, sw, N, K, r, g):
     """Oracle-side prepared weights -> device blob through dirotq_import_weights."""
     Wh_d = dev_bf16(O.bf16_bits(Wh)) if r else None
@@ -46,7 +64,7 @@ def gpu_rotate_quantize(x_bits, Qt_dev, r, g):
     K = x_bits.shape[1]
     xh_h = O.from_bf16_bits(host_bf16_bits(xh)) if r else np.zeros((x_bits.shape[0], 0), np.float32)
     if r < K:
-        qx = O.unpack_int4(xl.cpu().numpy())
+        qx = unpack_codes(xl.cpu().numpy())
         sx_h = np.ascontiguousarray(host_f16(sx).T)           # -> [M, G] like the oracle
     else:
         qx = np.zeros((x_bits.shape[0], 0), np.int8)

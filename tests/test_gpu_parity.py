@@ -9,7 +9,7 @@ from oracle import dirotq_oracle as O
 from paper_2605_16732_amd import binding as B
 from paper_2605_16732_amd import inputs as I
 
-from gpu_util import (check_codes_statistical, check_output, dev, dev_bf16, gpu_rotate_quantize, host_bf16_bits,
+from gpu_util import (pack_codes, unpack_codes, check_codes_statistical, check_output, dev, dev_bf16, gpu_rotate_quantize, host_bf16_bits,
                       host_f16, import_blob, layer_with_oracle)
 
 pytestmark = pytest.mark.gpu
@@ -134,7 +134,7 @@ def test_w4a4_integer_dot_is_exact(M, N, K, g):
     qx[0, :] = 7
     qw[0, :] = -7                                         # extreme: I = -49 g per group
     blob = import_blob(np.zeros((N, 0), np.float32), qw, np.ones((N, G), np.float16), N, K, 0, g)
-    xl = dev(O.pack_int4(qx))
+    xl = dev(pack_codes(qx))
     sx = dev(np.ones((G, M), np.float16))
     y = B.w4a4_gemm(None, xl, sx, blob, M, N, K, 0, g, out_dtype=torch.float32)
     torch.cuda.synchronize()
@@ -153,7 +153,7 @@ def test_w4a4_power_of_two_scales_exact():
     sx = (2.0 ** rng.integers(-3, 3, size=(M, G))).astype(np.float16)
     sw = (2.0 ** rng.integers(-4, 2, size=(N, G))).astype(np.float16)
     blob = import_blob(np.zeros((N, 0), np.float32), qw, sw, N, K, 0, g)
-    y = B.w4a4_gemm(None, dev(O.pack_int4(qx)), dev(np.ascontiguousarray(sx.T)), blob, M, N, K, 0, g,
+    y = B.w4a4_gemm(None, dev(pack_codes(qx)), dev(np.ascontiguousarray(sx.T)), blob, M, N, K, 0, g,
                     out_dtype=torch.float32)
     torch.cuda.synchronize()
     want, _ = O.combine(np.zeros((M, 0), np.float32), qx, sx, np.zeros((N, 0), np.float32), qw, sw, g)
@@ -181,7 +181,7 @@ def test_w4a4_gemm_matches_oracle_on_identical_inputs(M, N, K, r, g, use_bias):
     bias = O.round_to_bf16(rng.standard_normal(N).astype(np.float32)) if use_bias else None
     y32, ybf = O.combine(xh, qx, sx, Wh, qw, sw, g, bias)
     blob = import_blob(Wh, qw, sw, N, K, r, g)
-    args = (dev_bf16(O.bf16_bits(xh)) if r else None, dev(O.pack_int4(qx)) if r < K else None,
+    args = (dev_bf16(O.bf16_bits(xh)) if r else None, dev(pack_codes(qx)) if r < K else None,
             dev(np.ascontiguousarray(sx.T)) if r < K else None, blob, M, N, K, r, g)
     bias_d = dev_bf16(O.bf16_bits(bias)) if use_bias else None
     yf = B.w4a4_gemm(*args, bias=bias_d, out_dtype=torch.float32).cpu().numpy()
