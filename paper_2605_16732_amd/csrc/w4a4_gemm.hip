@@ -235,11 +235,12 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
         for (int v = 0; v < 16; v++) acc[i][j][v] = fmaf(I[slot][v], P[slot][v], acc[i][j][v]);
         asm volatile("" : "+v"(acc[i][j]));            // pin the sweep here (keeps I/P live ranges short)
       };
-      // the next stage's unpack work is spread over the last four tile sweeps of this stage
+      // the next stage's unpack work is spread over the tile sweeps of this stage
       constexpr int NSTEP = GPS * 4;
       auto stage_piece = [&](int step) {
-        if (step >= NSTEP - 4) {                             // (after the last stage: unused)
-          const int i = step - (NSTEP - 4);
+        // chunk i goes with step (i + 1) * NSTEP / 4 - 1: evenly spread over the stage
+        if ((step + 1) % (NSTEP / 4) == 0) {                 // (after the last stage: unused)
+          const int i = (step + 1) / (NSTEP / 4) - 1;
           sstore_piece(buf ^ 1, i);
           gload_piece(st2, i);
           if (step == NSTEP - 1) {                           // scales
