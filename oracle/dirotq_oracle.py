@@ -29,13 +29,18 @@ Readings where the paper is silent (each is listed in the design notes too):
     with "16-bit scaling factors");
   * scales are stored as IEEE fp16 and codes are computed against the *stored*
     scale, with the fixed fp32 operation sequence of `quantize_groups`;
-  * the quantizer reads the fp32 rotated activation, not a BF16-rounded copy.
+  * the quantizer reads the fp32 rotated activation, not a BF16-rounded copy;
+  * the asymmetric activation variant (`*_asym`, the form the paper's experiments use
+    for activations: z = min X, s = (max X - min X) / 15, codes in [0, 15]) stores the
+    zero-point as fp16 next to the fp16 scale and quantizes against the stored pair.
 
 Pins (see tests/test_oracle_*.py): hand-worked quantizer cases from the quantizer
 equation, nibble packing bytes, a pure-Python-loop brute force of the whole layer on
 tiny shapes, the identity X W = X V V^T W (exact mode, any r), reduction to a plain
 BF16 GEMM at r = K, reduction to plain per-group RTN at Q = I, quantizer error
-bounds.  Unpinned: absolute QSNR / image-quality numbers of the paper (they need
+bounds; for the asymmetric variant hand-worked cases, shift equivariance, its error
+bound, and a brute force that dequantizes every element (q s + z) and multiplies
+out, which pins the zero-point term of `combine_asym`.  Unpinned: absolute QSNR / image-quality numbers of the paper (they need
 its models and data) -- "parity unpinned" for those, none of which is computed here.
 """
 from __future__ import annotations
@@ -43,6 +48,7 @@ from __future__ import annotations
 import numpy as np
 
 QMAX = 7                       # 2^(4-1) - 1, quantizer equation, symmetric case
+UQMAX = 15                     # 2^4 - 1, quantizer equation, asymmetric case (q_min = 0)
 FP16_MAX = np.float32(65504.0)
 
 
@@ -131,6 +137,52 @@ def dequantize_groups(codes: np.ndarray, scales: np.ndarray, g: int) -> np.ndarr
 
 
 # --------------------------------------------------------------------------
+# the quantizer, asymmetric case  (quantizer equation: z = min X,
+# s = (max X - min X) / (q_max - q_min), q_min = 0, q_max = 2^4 - 1)
+# --------------------------------------------------------------------------
+def quantize_groups_asym(v: np.ndarray, g: int):
+    """Asymmetric UINT4 quantization of the last axis in groups of g.
+
+    v: float32 [..., C], C % g == 0.  Returns (codes uint8 [..., C] in [0,15],
+    scales float16 [..., C/g], zeros float16 [..., C/g]).  The dequantised value is
+    codes * float32(scale) + float32(zero).
+
+    Fixed IEEE-fp32 sequence:  mn = min v, mx = max v;  z16 = fp16(mn) (round to
+    nearest even, saturating at +-65504), zf = float32(z16);  s32 = (mx - mn) / 15
+    (fp32 subtraction, then fp32 division);  s16 = fp16(min(s32, 65504));
+    sf = float32(s16);  sf == 0 -> all codes 0;  else inv = 1 / sf (fp32 division),
+    t = (v - zf) * inv (fp32 subtraction, then fp32 product),
+    code = clip(rint(t), 0, 15) with rint = ties to even.
+    """
+    v = np.ascontiguousarray(v, dtype=np.float32)
+    C = v.shape[-1]
+    assert C % g == 0
+    vg = v.reshape(v.shape[:-1] + (C // g, g))
+    mn = np.min(vg, axis=-1)
+    mx = np.max(vg, axis=-1)
+    z16 = np.clip(mn, -FP16_MAX, FP16_MAX).astype(np.float16)        # RNE
+    zf = z16.astype(np.float32)
+    s32 = ((mx - mn).astype(np.float32) / np.float32(UQMAX)).astype(np.float32)
+    s32 = np.minimum(s32, FP16_MAX)
+    s16 = s32.astype(np.float16)
+    sf = s16.astype(np.float32)
+    with np.errstate(divide="ignore"):
+        inv = (np.float32(1.0) / sf).astype(np.float32)
+    inv = np.where(sf == 0, np.float32(0.0), inv).astype(np.float32)
+    t = ((vg - zf[..., None]).astype(np.float32) * inv[..., None]).astype(np.float32)
+    q = np.clip(np.rint(t), 0, UQMAX).astype(np.uint8)
+    return q.reshape(v.shape), s16, z16
+
+
+def dequantize_groups_asym(codes, scales, zeros, g: int) -> np.ndarray:
+    """codes * scale + zero, in float64."""
+    c = np.asarray(codes).astype(np.float64)
+    s = np.repeat(np.asarray(scales).astype(np.float64), g, axis=-1)
+    z = np.repeat(np.asarray(zeros).astype(np.float64), g, axis=-1)
+    return c * s + z
+
+
+# --------------------------------------------------------------------------
 # offline: fuse the rotation into the weights, split, quantize
 # ("the transpose of the combined rotation can be absorbed into the weights
 #  offline"; RTN stands in for GPTQ on the residual weights)
@@ -214,6 +266,62 @@ def linear(x, Q, Wh, qw, sw, r, g, bias=None):
     xh, qx, sx = split_quantize(xhat, r, g)
     y32, y = combine(xh, qx, sx, Wh, qw, sw, g, bias)
     return dict(xhat=xhat, xh=xh, qx=qx, sx=sx, y32=y32, y=y)
+
+
+# --------------------------------------------------------------------------
+# asymmetric activations: the same layer with the quantizer's z term kept
+# ("the asymmetric case follows analogously with an additional z term";
+#  weights stay symmetric)
+# --------------------------------------------------------------------------
+def split_quantize_asym(xhat: np.ndarray, r: int, g: int):
+    """Returns (xh float32 bf16-valued [M,r], qx uint8 [M,K-r] in [0,15],
+    sx float16 [M,G], zx float16 [M,G])."""
+    xh = round_to_bf16(xhat[:, :r])
+    if r < xhat.shape[1]:
+        qx, sx, zx = quantize_groups_asym(xhat[:, r:], g)
+    else:
+        qx = np.zeros((xhat.shape[0], 0), np.uint8)
+        sx = np.zeros((xhat.shape[0], 0), np.float16)
+        zx = np.zeros((xhat.shape[0], 0), np.float16)
+    return xh, qx, sx, zx
+
+
+def weight_group_sums(qw: np.ndarray, g: int) -> np.ndarray:
+    """sum of the weight codes of each group: int64 [N, G]."""
+    N, C = qw.shape
+    return qw.astype(np.int64).reshape(N, C // g, g).sum(axis=-1)
+
+
+def combine_asym(xh, qx, sx, zx, Wh, qw, sw, g, bias=None):
+    """With x~[m,k] = sx[m,j] qx[m,k] + zx[m,j] and w~[n,k] = sw[n,j] qw[n,k]:
+    sum_k x~ w~ = sum_j ( sx sw I[m,n,j] + zx[m,j] sw[n,j] sum_{k in j} qw[n,k] ).
+    y32 = sum_{k<r} xh Wh + that (+ bias), float64, rounded once to float32."""
+    M = xh.shape[0]
+    N = Wh.shape[0]
+    acc = np.asarray(xh, np.float64) @ np.asarray(Wh, np.float64).T if xh.shape[1] else np.zeros((M, N))
+    C = qx.shape[1]
+    G = C // g if C else 0
+    sx64 = np.asarray(sx).astype(np.float64)
+    zx64 = np.asarray(zx).astype(np.float64)
+    sw64 = np.asarray(sw).astype(np.float64)
+    wsum = weight_group_sums(qw, g).astype(np.float64) if G else np.zeros((N, 0))
+    for j in range(G):
+        a = qx[:, j * g:(j + 1) * g].astype(np.float64)
+        b = qw[:, j * g:(j + 1) * g].astype(np.float64)
+        I = a @ b.T
+        acc = acc + (sx64[:, j][:, None] * sw64[:, j][None, :]) * I
+        acc = acc + zx64[:, j][:, None] * (sw64[:, j] * wsum[:, j])[None, :]
+    if bias is not None:
+        acc = acc + np.asarray(bias, np.float64)[None, :]
+    y32 = acc.astype(np.float32)
+    return y32, round_to_bf16(y32)
+
+
+def linear_asym(x, Q, Wh, qw, sw, r, g, bias=None):
+    xhat = rotate(x, Q)
+    xh, qx, sx, zx = split_quantize_asym(xhat, r, g)
+    y32, y = combine_asym(xh, qx, sx, zx, Wh, qw, sw, g, bias)
+    return dict(xhat=xhat, xh=xh, qx=qx, sx=sx, zx=zx, y32=y32, y=y)
 
 
 # --------------------------------------------------------------------------

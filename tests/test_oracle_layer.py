@@ -228,3 +228,91 @@ def test_quantization_error_trend_on_outlier_activations():
     Wh, qw, sw = O.prepare_weights(L.W, eye, 0, 32)
     plain = O.qsnr_db(ref, O.linear(x, eye, Wh, qw, sw, 0, 32)["y32"])
     assert q[32] > plain + 3.0
+
+
+# ---------------------------------------------------------------------------
+# asymmetric activations
+# ---------------------------------------------------------------------------
+def _quant_asym(vals):
+    mn, mx = min(vals), max(vals)
+    zf = _f16(max(-65504.0, min(65504.0, mn)))
+    sf = _f16(min(_f32(_f32(mx - mn) / 15.0), 65504.0))
+    if sf == 0.0:
+        return [0] * len(vals), 0.0, zf
+    inv = _f32(1.0 / sf)
+    return [max(0, min(15, round(_f32(_f32(v - zf) * inv)))) for v in vals], sf, zf
+
+
+def _brute_layer_asym(x, Q, Q32, W, r, g, bias=None):
+    """The layer with asymmetric activations written as the quantizer equation says: every
+    activation is replaced by its dequantised value q s + z, every weight by q_w s_w, and
+    the products are summed exactly -- no zero-point algebra here."""
+    M, K, N = len(x), len(x[0]), len(W)
+    G = (K - r) // g
+    Wp = [[_f32(float(sum(Fraction(W[n][k]) * Fraction(Q32[k][c]) for k in range(K))))
+           for c in range(K)] for n in range(N)]
+    Wh = [[_bf16(Wp[n][c]) for c in range(r)] for n in range(N)]
+    wt = []                                  # dequantised 4-bit weights, exact
+    for n in range(N):
+        row = []
+        for j in range(G):
+            c, s = _quant(Wp[n][r + j * g: r + (j + 1) * g])
+            row += [Fraction(ci) * Fraction(s) for ci in c]
+        wt.append(row)
+    y = []
+    for m in range(M):
+        xhat = [_f32(float(sum(Fraction(x[m][k]) * Fraction(Q[k][c]) for k in range(K))))
+                for c in range(K)]
+        xh = [_bf16(v) for v in xhat[:r]]
+        xt = []
+        for j in range(G):
+            c, s, z = _quant_asym(xhat[r + j * g: r + (j + 1) * g])
+            xt += [Fraction(ci) * Fraction(s) + Fraction(z) for ci in c]
+        row = []
+        for n in range(N):
+            acc = sum(Fraction(xh[k]) * Fraction(Wh[n][k]) for k in range(r))
+            acc += sum(xt[k] * wt[n][k] for k in range(K - r))
+            if bias is not None:
+                acc += Fraction(bias[n])
+            row.append(_f32(float(acc)))
+        y.append(row)
+    return np.array(y, np.float32)
+
+
+@pytest.mark.parametrize("M,K,N,r,g", [(3, 16, 5, 0, 4), (3, 16, 5, 4, 4), (2, 12, 4, 4, 8), (4, 20, 3, 4, 16)])
+def test_asym_brute_force_tiny(M, K, N, r, g):
+    x, Q, Q32, W = _tiny(200 + K + r, M, K, N)
+    x = O.round_to_bf16(x + np.float32(1.5))          # shifted: the zero-points matter
+    bias = np.linspace(-1, 1, N).astype(np.float32)
+    want = _brute_layer_asym(x.tolist(), Q.tolist(), Q32.tolist(), W.tolist(), r, g, bias.tolist())
+    Wh, qw, sw = O.prepare_weights(W, Q32, r, g)
+    got = O.linear_asym(x, Q, Wh, qw, sw, r, g, bias)
+    np.testing.assert_allclose(got["y32"], want, rtol=2.0 ** -22, atol=1e-30)
+    assert got["qx"].dtype == np.uint8 and got["qx"].max() <= 15
+    # the zero-point term is not small here: dropping it must be visible
+    no_z, _ = O.combine_asym(got["xh"], got["qx"], got["sx"], np.zeros_like(got["zx"]), Wh, qw, sw, g, bias)
+    assert np.abs(no_z - want).max() > 1e-3 * np.abs(want).max()
+
+
+def test_asym_equals_symmetric_layer_on_dequantised_inputs():
+    # combine_asym on (q, s, z) == a plain float64 GEMM of the dequantised operands
+    rng = np.random.default_rng(8)
+    M, N, C, g = 6, 5, 32, 8
+    xhat = (rng.standard_normal((M, C)) * 3 + 2).astype(np.float32)
+    Wp = rng.standard_normal((N, C)).astype(np.float32)
+    qx, sx, zx = O.quantize_groups_asym(xhat, g)
+    qw, sw = O.quantize_groups(Wp, g)
+    y32, _ = O.combine_asym(np.zeros((M, 0), np.float32), qx, sx, zx, np.zeros((N, 0), np.float32), qw, sw, g)
+    want = O.dequantize_groups_asym(qx, sx, zx, g) @ O.dequantize_groups(qw, sw, g).T
+    np.testing.assert_allclose(y32, want.astype(np.float32), rtol=2.0 ** -22, atol=1e-30)
+
+
+def test_asym_is_closer_than_symmetric_on_shifted_activations():
+    # activations with a per-group offset: the asymmetric grid spends its 16 levels on the range actually used
+    rng = np.random.default_rng(9)
+    v = (rng.standard_normal((64, 128)) + 4.0).astype(np.float32)
+    qs, ss = O.quantize_groups(v, 64)
+    qa, sa, za = O.quantize_groups_asym(v, 64)
+    err_sym = np.abs(O.dequantize_groups(qs, ss, 64) - v).mean()
+    err_asym = np.abs(O.dequantize_groups_asym(qa, sa, za, 64) - v).mean()
+    assert err_asym < 0.5 * err_sym

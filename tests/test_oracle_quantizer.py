@@ -163,3 +163,103 @@ def test_bf16_rounding():
     x = np.random.default_rng(0).standard_normal(10000).astype(np.float32) * 37.0
     t = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
     np.testing.assert_array_equal(O.round_to_bf16(x), t)
+
+
+# ---------------------------------------------------------------------------
+# asymmetric variant (z = min X, s = (max X - min X) / 15, codes in [0, 15])
+# ---------------------------------------------------------------------------
+GOLDEN_ASYM = os.path.join(os.path.dirname(__file__), "golden", "quantizer_asym_cases.txt")
+
+
+def _asym_cases():
+    out = []
+    with open(GOLDEN_ASYM) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            vals, s_hex, z_hex, codes = [p.strip() for p in line.split("|")]
+            out.append((np.array([float(v) for v in vals.split()], np.float32), int(s_hex, 16), int(z_hex, 16),
+                        np.array([int(c) for c in codes.split()], np.uint8)))
+    return out
+
+
+def test_asym_qmax_is_the_papers():
+    # quantizer equation: q_min = 0, q_max = 2^k - 1 for k-bit asymmetric integers
+    assert O.UQMAX == 2 ** 4 - 1 == 15
+
+
+@pytest.mark.parametrize("vals,s_bits,z_bits,codes", _asym_cases())
+def test_asym_hand_worked_cases(vals, s_bits, z_bits, codes):
+    q, s, z = O.quantize_groups_asym(vals[None, :], g=len(vals))
+    assert s.dtype == np.float16 and z.dtype == np.float16 and q.dtype == np.uint8
+    assert int(s.view(np.uint16)[0, 0]) == s_bits
+    assert int(z.view(np.uint16)[0, 0]) == z_bits
+    np.testing.assert_array_equal(q[0], codes)
+
+
+def _f16(x):
+    return struct.unpack("e", struct.pack("e", x))[0]
+
+
+def test_asym_against_pure_python_sequence():
+    # the documented fp32 operation sequence, re-done with Python floats rounded by struct
+    rng = np.random.default_rng(11)
+    v = (rng.standard_normal((40, 24)) * rng.lognormal(0, 2, (40, 1)) + rng.normal(0, 3, (40, 1))).astype(np.float32)
+    q, s, z = O.quantize_groups_asym(v, 8)
+    for i in range(v.shape[0]):
+        for j in range(3):
+            grp = [float(t) for t in v[i, j * 8:(j + 1) * 8]]
+            mn, mx = min(grp), max(grp)
+            zf = _f16(max(-65504.0, min(65504.0, mn)))
+            sf = _f16(min(_f32(_f32(mx - mn) / 15.0), 65504.0))
+            assert float(s[i, j]) == sf and float(z[i, j]) == zf
+            if sf == 0.0:
+                want = [0] * 8
+            else:
+                inv = _f32(1.0 / sf)
+                want = [max(0, min(15, round(_f32(_f32(t - zf) * inv)))) for t in grp]
+            assert list(q[i, j * 8:(j + 1) * 8]) == want
+
+
+@pytest.mark.parametrize("g", [4, 32, 64])
+def test_asym_invariants(g):
+    rng = np.random.default_rng(5 + g)
+    v = (rng.standard_normal((64, 2 * g)) * rng.lognormal(0, 1.5, (64, 1)) + rng.normal(0, 2, (64, 1))).astype(np.float32)
+    q, s, z = O.quantize_groups_asym(v, g)
+    assert q.min() >= 0 and q.max() <= 15
+    vg = v.reshape(64, 2, g).astype(np.float64)
+    sf, zf = s.astype(np.float64), z.astype(np.float64)
+    # the stored pair is the definition's pair up to fp16 rounding (relative 2^-11)
+    np.testing.assert_allclose(zf, vg.min(-1), rtol=2.0 ** -11, atol=2.0 ** -25)
+    np.testing.assert_allclose(sf, (vg.max(-1) - vg.min(-1)) / 15, rtol=2.0 ** -10, atol=2.0 ** -25)
+    # error of the dequantised value: half a step, plus what the fp16 roundings of z and s move the grid
+    # (at most |z - min| at the bottom and 15 |s - s_exact| + |z - min| at the top)
+    deq = O.dequantize_groups_asym(q, s, z, g).reshape(64, 2, g)
+    slack = np.abs(zf - vg.min(-1)) + 15 * np.abs(sf - (vg.max(-1) - vg.min(-1)) / 15)
+    bound = sf / 2 * (1 + 2.0 ** -20) + slack + 1e-30
+    assert np.all(np.abs(deq - vg) <= bound[..., None])
+    # the smallest element gets code 0 and the largest 15 (unless the group is constant)
+    live = sf > 0
+    amin = np.take_along_axis(q.reshape(64, 2, g), vg.argmin(-1)[..., None], -1)[..., 0]
+    amax = np.take_along_axis(q.reshape(64, 2, g), vg.argmax(-1)[..., None], -1)[..., 0]
+    assert np.all(amin[live] == 0) and np.all(amax[live] >= 14)
+
+
+def test_asym_shift_equivariance_on_a_dyadic_grid():
+    # values on a coarse dyadic grid: adding a grid constant moves z by it and leaves s and the codes alone
+    rng = np.random.default_rng(3)
+    v = (rng.integers(-40, 41, (50, 16)) * 0.25).astype(np.float32)
+    q0, s0, z0 = O.quantize_groups_asym(v, 16)
+    q1, s1, z1 = O.quantize_groups_asym(v + np.float32(6.5), 16)
+    np.testing.assert_array_equal(q0, q1)
+    np.testing.assert_array_equal(s0.view(np.uint16), s1.view(np.uint16))
+    np.testing.assert_array_equal(z1.astype(np.float32), z0.astype(np.float32) + np.float32(6.5))
+
+
+def test_asym_of_a_symmetric_two_point_group():
+    # {-a, +a}: z = -a, s = 2a/15, codes 0 and 15; dequantised ends are -a and -a + 15 s
+    a = np.float32(3.75)
+    q, s, z = O.quantize_groups_asym(np.array([[-a, a, -a, a]], np.float32), 4)
+    np.testing.assert_array_equal(q[0], [0, 15, 0, 15])
+    assert float(z[0, 0]) == -3.75 and float(s[0, 0]) == 0.5
