@@ -58,6 +58,8 @@ def main() -> int:
                          "(configs[3]); ablation = rank/group grid on the FLUX fc2 shape (configs[4])")
     ap.add_argument("--residual-rotation", action="store_true",
                     help="fold a random orthogonal rotation of the 4-bit subspace into Q (Q = [U_h, U_l R])")
+    ap.add_argument("--asym", action="store_true",
+                    help="asymmetric activation quantizer (zero-point min, 16 unsigned levels): the *_asym entry points")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise copy of known size (256 MiB read + 256 MiB written), "
                          "the reference the FETCH_SIZE / WRITE_SIZE counters are scaled by")
@@ -112,6 +114,8 @@ def main() -> int:
         parts = (torch.empty((shp.M, shp.r), dtype=torch.bfloat16, device=dev),
                  torch.empty((shp.M, (shp.K - shp.r) // 2), dtype=torch.uint8, device=dev),
                  torch.empty((G, shp.M), dtype=torch.float16, device=dev))
+        if args.asym:
+            parts = parts + (torch.empty((G, shp.M), dtype=torch.float16, device=dev),)
         layers.append(dict(shape=shp, x=x, Qt=Qt, blob=blob, ws=ws, y=y, Wb=Wb, parts=parts, host=L))
         torch.cuda.synchronize()
         log(f"inputs for {shp.name} ready ({time.time() - t0:.0f} s)")
@@ -124,10 +128,14 @@ def main() -> int:
         torch.cuda.synchronize()
         del ca, cb
 
+    f_linear = B.linear_asym if args.asym else B.linear
+    f_rq = B.rotate_quantize_asym if args.asym else B.rotate_quantize
+    f_gemm = B.w4a4_gemm_asym if args.asym else B.w4a4_gemm
+
     def step():
         for Ld in layers:
             s = Ld["shape"]
-            B.linear(Ld["x"], Ld["Qt"], Ld["blob"], s.N, s.r, s.g, workspace=Ld["ws"], out=Ld["y"])
+            f_linear(Ld["x"], Ld["Qt"], Ld["blob"], s.N, s.r, s.g, workspace=Ld["ws"], out=Ld["y"])
 
     # ---- whole-step timing -----------------------------------------------------------
     for _ in range(args.warmup):
@@ -165,10 +173,10 @@ def main() -> int:
     for Ld in layers:
         s = Ld["shape"]
         alg = algorithmic(s)
-        xh, xl, sx = Ld["parts"]
-        tA = time_calls(lambda: B.rotate_quantize(Ld["x"], Ld["Qt"], s.r, s.g, out=(xh, xl, sx)), reps)
-        tB = time_calls(lambda: B.w4a4_gemm(xh, xl, sx, Ld["blob"], s.M, s.N, s.K, s.r, s.g, out=Ld["y"]), reps)
-        tL = time_calls(lambda: B.linear(Ld["x"], Ld["Qt"], Ld["blob"], s.N, s.r, s.g, workspace=Ld["ws"],
+        parts = Ld["parts"]
+        tA = time_calls(lambda: f_rq(Ld["x"], Ld["Qt"], s.r, s.g, out=parts), reps)
+        tB = time_calls(lambda: f_gemm(*parts, Ld["blob"], s.M, s.N, s.K, s.r, s.g, out=Ld["y"]), reps)
+        tL = time_calls(lambda: f_linear(Ld["x"], Ld["Qt"], Ld["blob"], s.N, s.r, s.g, workspace=Ld["ws"],
                                          out=Ld["y"]), reps)
         WbT = Ld["Wb"]
         yb = torch.empty_like(Ld["y"])
@@ -265,7 +273,8 @@ def main() -> int:
                                 "small": "configs[0]: M=256, K=N=1152",
                                 "sweep": "configs[3]: token sweep on the PixArt fc1 shape, M in {1024..32768}",
                                 "ablation": "configs[4]: rank/group grid on the FLUX fc2 shape"}[args.workload],
-                   "seed": 0, "effective_ops_per_step": total_ops, "residual_rotation": args.residual_rotation},
+                   "seed": 0, "effective_ops_per_step": total_ops, "residual_rotation": args.residual_rotation,
+                   "activation_quantizer": "asymmetric" if args.asym else "symmetric"},
         "speedup_vs_bf16_gemm": round(bf16_ms / ms_per_step, 4),
         "bf16_gemm_ms_per_step": round(bf16_ms, 4),
         "roofline": {k: (round(v, 5) if isinstance(v, float) else v) for k, v in roofline.items()},

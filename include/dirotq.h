@@ -147,6 +147,34 @@ int dirotq_linear(const uint16_t* x_bf16, const uint16_t* Qt_bf16, const void* b
                   const uint16_t* bias_bf16, int M, int N, int K, int r, int g,
                   uint16_t* y_bf16 /*out*/, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- online, asymmetric activations ------------------------------------------- */
+/*
+ * The same three calls with the asymmetric form of the Section 3 quantizer for the
+ * activations (the form the paper's experiments use for them; weights stay
+ * symmetric): per token and group z = min, s = (max - min) / 15, code =
+ * clip(round-half-even((v - z) / s), 0, 15).  In IEEE fp32: z16 = fp16_rne(clamp(min,
+ * +-65504)), s32 = (max - min) / 15, s16 = fp16_rne(min(s32, 65504)), inv = 1 / float(s16)
+ * (0 when s16 == 0), code = clip(rint((v - float(z16)) * inv), 0, 15).
+ * The dequantized activation is code * s + z, so the product gains the zero-point term
+ *   y[m,n] += sum_j float(zx[j,m]) * float(sw[n,j]) * sum_{k in group j} q_w[n,k];
+ * the per-group sums of the weight codes are part of every prepared blob.
+ *   xl_packed[M,(K-r)/2]  two unsigned nibbles per byte, even channel in bits 0-3
+ *   sx_fp16, zx_fp16 [G,M]  group-major scales and zero-points
+ * Pointer, shape and error rules are those of the symmetric calls.
+ */
+int dirotq_rotate_quantize_asym(const uint16_t* x_bf16, const uint16_t* Qt_bf16, int M, int K, int r, int g,
+                                uint16_t* xh_bf16, uint8_t* xl_packed, uint16_t* sx_fp16,
+                                uint16_t* zx_fp16, void* stream);
+
+int dirotq_w4a4_gemm_asym(const uint16_t* xh_bf16, const uint8_t* xl_packed, const uint16_t* sx_fp16,
+                          const uint16_t* zx_fp16, const void* blob, const uint16_t* bias_bf16, int M, int N,
+                          int K, int r, int g, void* y /*out*/, int y_dtype, void* stream);
+
+/* workspace: dirotq_workspace_bytes bytes (it has room for the zero-points). */
+int dirotq_linear_asym(const uint16_t* x_bf16, const uint16_t* Qt_bf16, const void* blob,
+                       const uint16_t* bias_bf16, int M, int N, int K, int r, int g,
+                       uint16_t* y_bf16 /*out*/, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -35,6 +35,9 @@ SIGNATURES = {
     "dirotq_rotate_quantize": (_c_int, [_c_void_p, _c_void_p] + [_c_int] * 4 + [_c_void_p] * 4),
     "dirotq_w4a4_gemm": (_c_int, [_c_void_p] * 5 + [_c_int] * 5 + [_c_void_p, _c_int, _c_void_p]),
     "dirotq_linear": (_c_int, [_c_void_p] * 4 + [_c_int] * 5 + [_c_void_p, _c_void_p, _c_size_t, _c_void_p]),
+    "dirotq_rotate_quantize_asym": (_c_int, [_c_void_p, _c_void_p] + [_c_int] * 4 + [_c_void_p] * 5),
+    "dirotq_w4a4_gemm_asym": (_c_int, [_c_void_p] * 6 + [_c_int] * 5 + [_c_void_p, _c_int, _c_void_p]),
+    "dirotq_linear_asym": (_c_int, [_c_void_p] * 4 + [_c_int] * 5 + [_c_void_p, _c_void_p, _c_size_t, _c_void_p]),
 }
 
 
@@ -170,4 +173,42 @@ def linear(x, Qt, blob, N, r, g, bias=None, workspace=None, out=None):
     y = out if out is not None else _new((M, N), torch.bfloat16, x)
     _check(lib().dirotq_linear(_ptr(x), _ptr(Qt), _ptr(blob), _ptr(bias), M, N, K, r, g, _ptr(y),
                                _ptr(workspace), workspace.numel(), _stream()), "dirotq_linear")
+    return y
+
+
+def rotate_quantize_asym(x, Qt, r, g, out=None):
+    """x bf16 [M,K], Qt bf16 [K,K] -> (xh bf16 [M,r], xl uint8 [M,(K-r)/2] unsigned nibbles,
+    sx fp16 [G,M], zx fp16 [G,M])."""
+    M, K = x.shape
+    G = (K - r) // g
+    if out is None:
+        out = (_new((M, r), torch.bfloat16, x), _new((M, (K - r) // 2), torch.uint8, x),
+               _new((G, M), torch.float16, x), _new((G, M), torch.float16, x))
+    xh, xl, sx, zx = out
+    low = r < K
+    _check(lib().dirotq_rotate_quantize_asym(_ptr(x), _ptr(Qt), M, K, r, g, _ptr(xh) if r else None,
+                                             _ptr(xl) if low else None, _ptr(sx) if low else None,
+                                             _ptr(zx) if low else None, _stream()), "dirotq_rotate_quantize_asym")
+    return xh, xl, sx, zx
+
+
+def w4a4_gemm_asym(xh, xl, sx, zx, blob, M, N, K, r, g, bias=None, out_dtype=torch.bfloat16, out=None):
+    y = out if out is not None else torch.empty((M, N), dtype=out_dtype, device=blob.device)
+    code = {torch.bfloat16: 0, torch.float32: 1}[y.dtype]
+    low = r < K
+    _check(lib().dirotq_w4a4_gemm_asym(_ptr(xh) if r else None, _ptr(xl) if low else None,
+                                       _ptr(sx) if low else None, _ptr(zx) if low else None, _ptr(blob),
+                                       _ptr(bias), M, N, K, r, g, _ptr(y), code, _stream()),
+           "dirotq_w4a4_gemm_asym")
+    return y
+
+
+def linear_asym(x, Qt, blob, N, r, g, bias=None, workspace=None, out=None):
+    M, K = x.shape
+    nws = workspace_bytes(M, K, r, g)
+    if workspace is None:
+        workspace = _new((nws,), torch.uint8, x)
+    y = out if out is not None else _new((M, N), torch.bfloat16, x)
+    _check(lib().dirotq_linear_asym(_ptr(x), _ptr(Qt), _ptr(blob), _ptr(bias), M, N, K, r, g, _ptr(y),
+                                    _ptr(workspace), workspace.numel(), _stream()), "dirotq_linear_asym")
     return y

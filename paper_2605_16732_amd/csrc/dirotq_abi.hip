@@ -118,7 +118,7 @@ int dirotq_rotate_quantize(const uint16_t* x_bf16, const uint16_t* Qt_bf16, int 
   if (misaligned(x_bf16) || misaligned(Qt_bf16) || misaligned(xh_bf16) || misaligned(xl_packed) ||
       misaligned(sx_fp16))
     return DIROTQ_ERR_ALIGN;
-  return launch_rotate_quantize(x_bf16, Qt_bf16, M, K, r, g, xh_bf16, xl_packed, sx_fp16,
+  return launch_rotate_quantize(x_bf16, Qt_bf16, M, K, r, g, xh_bf16, xl_packed, sx_fp16, nullptr,
                                 (hipStream_t)stream);
 }
 
@@ -135,7 +135,7 @@ int dirotq_w4a4_gemm(const uint16_t* xh_bf16, const uint8_t* xl_packed, const ui
   if (misaligned(xh_bf16) || misaligned(xl_packed) || misaligned(sx_fp16) || misaligned(blob) ||
       misaligned(bias_bf16) || misaligned(y))
     return DIROTQ_ERR_ALIGN;
-  return launch_w4a4_gemm(xh_bf16, xl_packed, sx_fp16, blob, bias_bf16, M, N, K, r, g, y, y_dtype,
+  return launch_w4a4_gemm(xh_bf16, xl_packed, sx_fp16, nullptr, blob, bias_bf16, M, N, K, r, g, y, y_dtype,
                           (hipStream_t)stream);
 }
 
@@ -155,9 +155,66 @@ int dirotq_linear(const uint16_t* x_bf16, const uint16_t* Qt_bf16, const void* b
   uint16_t* xh = (uint16_t*)(ws + L.off_xh);
   uint8_t* xl = (uint8_t*)(ws + L.off_xl);
   uint16_t* sx = (uint16_t*)(ws + L.off_sx);
-  st = launch_rotate_quantize(x_bf16, Qt_bf16, M, K, r, g, xh, xl, sx, (hipStream_t)stream);
+  st = launch_rotate_quantize(x_bf16, Qt_bf16, M, K, r, g, xh, xl, sx, nullptr, (hipStream_t)stream);
   if (st) return st;
-  return launch_w4a4_gemm(xh, xl, sx, blob, bias_bf16, M, N, K, r, g, y_bf16, 0, (hipStream_t)stream);
+  return launch_w4a4_gemm(xh, xl, sx, nullptr, blob, bias_bf16, M, N, K, r, g, y_bf16, 0, (hipStream_t)stream);
+}
+
+int dirotq_rotate_quantize_asym(const uint16_t* x_bf16, const uint16_t* Qt_bf16, int M, int K, int r, int g,
+                                uint16_t* xh_bf16, uint8_t* xl_packed, uint16_t* sx_fp16, uint16_t* zx_fp16,
+                                void* stream) {
+  int st = check_shape(M, 1, K, r, g);
+  if (st) return st;
+  if (M == 0) return DIROTQ_OK;
+  if (!x_bf16 || !Qt_bf16) return DIROTQ_ERR_NULL;
+  if (r > 0 && !xh_bf16) return DIROTQ_ERR_NULL;
+  if (r < K && (!xl_packed || !sx_fp16 || !zx_fp16)) return DIROTQ_ERR_NULL;
+  if (misaligned(x_bf16) || misaligned(Qt_bf16) || misaligned(xh_bf16) || misaligned(xl_packed) ||
+      misaligned(sx_fp16) || misaligned(zx_fp16))
+    return DIROTQ_ERR_ALIGN;
+  if (r == K) return launch_rotate_quantize(x_bf16, Qt_bf16, M, K, r, g, xh_bf16, nullptr, nullptr, nullptr,
+                                            (hipStream_t)stream);   // no 4-bit part: nothing to quantize
+  return launch_rotate_quantize(x_bf16, Qt_bf16, M, K, r, g, xh_bf16, xl_packed, sx_fp16, zx_fp16,
+                                (hipStream_t)stream);
+}
+
+int dirotq_w4a4_gemm_asym(const uint16_t* xh_bf16, const uint8_t* xl_packed, const uint16_t* sx_fp16,
+                          const uint16_t* zx_fp16, const void* blob, const uint16_t* bias_bf16, int M, int N,
+                          int K, int r, int g, void* y, int y_dtype, void* stream) {
+  int st = check_shape(M, N, K, r, g);
+  if (st) return st;
+  if (y_dtype != 0 && y_dtype != 1) return DIROTQ_ERR_UNSUPPORTED;
+  if (M == 0) return DIROTQ_OK;
+  if (!blob || !y) return DIROTQ_ERR_NULL;
+  if (r > 0 && !xh_bf16) return DIROTQ_ERR_NULL;
+  if (r < K && (!xl_packed || !sx_fp16 || !zx_fp16)) return DIROTQ_ERR_NULL;
+  if (misaligned(xh_bf16) || misaligned(xl_packed) || misaligned(sx_fp16) || misaligned(zx_fp16) ||
+      misaligned(blob) || misaligned(bias_bf16) || misaligned(y))
+    return DIROTQ_ERR_ALIGN;
+  return launch_w4a4_gemm(xh_bf16, xl_packed, sx_fp16, r < K ? zx_fp16 : nullptr, blob, bias_bf16, M, N, K, r, g, y,
+                          y_dtype, (hipStream_t)stream);
+}
+
+int dirotq_linear_asym(const uint16_t* x_bf16, const uint16_t* Qt_bf16, const void* blob,
+                       const uint16_t* bias_bf16, int M, int N, int K, int r, int g, uint16_t* y_bf16,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+  int st = check_shape(M, N, K, r, g);
+  if (st) return st;
+  if (M == 0) return DIROTQ_OK;
+  if (!x_bf16 || !Qt_bf16 || !blob || !y_bf16 || !workspace) return DIROTQ_ERR_NULL;
+  if (misaligned(x_bf16) || misaligned(Qt_bf16) || misaligned(blob) || misaligned(bias_bf16) ||
+      misaligned(y_bf16) || ((uintptr_t)workspace & (kAlign - 1)) != 0)
+    return DIROTQ_ERR_ALIGN;
+  const WorkspaceLayout L = workspace_layout(M, K, r, g);
+  if (workspace_bytes < L.bytes) return DIROTQ_ERR_WORKSPACE;
+  char* ws = (char*)workspace;
+  uint16_t* xh = (uint16_t*)(ws + L.off_xh);
+  uint8_t* xl = (uint8_t*)(ws + L.off_xl);
+  uint16_t* sx = (uint16_t*)(ws + L.off_sx);
+  uint16_t* zx = r < K ? (uint16_t*)(ws + L.off_zx) : nullptr;
+  st = launch_rotate_quantize(x_bf16, Qt_bf16, M, K, r, g, xh, xl, sx, zx, (hipStream_t)stream);
+  if (st) return st;
+  return launch_w4a4_gemm(xh, xl, sx, zx, blob, bias_bf16, M, N, K, r, g, y_bf16, 0, (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -24,8 +24,10 @@ inline size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a
 //   wh    bf16 [N][r]            16-bit branch of W' = W Q
 //   codes u8   [N][(K-r)/2]      INT4 codes of W'[:, r:], two per byte (even channel low)
 //   sw    fp16 [G][N]            group-major scales
+//   wsum  i16  [G][N]            sum of the codes of each group (zero-point term of the
+//                                asymmetric-activation product)
 struct BlobLayout {
-  size_t off_wh, off_codes, off_sw, bytes;
+  size_t off_wh, off_codes, off_sw, off_wsum, bytes;
 };
 inline BlobLayout blob_layout(int N, int K, int r, int g) {
   BlobLayout L;
@@ -33,14 +35,15 @@ inline BlobLayout blob_layout(int N, int K, int r, int g) {
   L.off_wh = 0;
   L.off_codes = align_up((size_t)N * r * 2);
   L.off_sw = L.off_codes + align_up((size_t)N * (K - r) / 2);
-  L.bytes = L.off_sw + align_up(G * N * 2);
+  L.off_wsum = L.off_sw + align_up(G * N * 2);
+  L.bytes = L.off_wsum + align_up(G * N * 2);
   if (L.bytes == 0) L.bytes = kAlign;
   return L;
 }
 
-// Workspace of dirotq_linear: xh bf16 [M][r] | xl u8 [M][(K-r)/2] | sx fp16 [G][M].
+// Workspace of dirotq_linear[_asym]: xh bf16 [M][r] | xl u8 [M][(K-r)/2] | sx fp16 [G][M] | zx fp16 [G][M].
 struct WorkspaceLayout {
-  size_t off_xh, off_xl, off_sx, bytes;
+  size_t off_xh, off_xl, off_sx, off_zx, bytes;
 };
 inline WorkspaceLayout workspace_layout(int M, int K, int r, int g) {
   WorkspaceLayout L;
@@ -48,7 +51,8 @@ inline WorkspaceLayout workspace_layout(int M, int K, int r, int g) {
   L.off_xh = 0;
   L.off_xl = align_up((size_t)M * r * 2);
   L.off_sx = L.off_xl + align_up((size_t)M * (K - r) / 2);
-  L.bytes = L.off_sx + align_up(G * M * 2);
+  L.off_zx = L.off_sx + align_up(G * M * 2);
+  L.bytes = L.off_zx + align_up(G * M * 2);
   if (L.bytes == 0) L.bytes = kAlign;
   return L;
 }
@@ -58,11 +62,12 @@ inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
 int hip_failed(hipError_t e);                               // records e, returns DIROTQ_ERR_HIP
 
 // kernel launchers (arguments already validated)
+// zx == nullptr selects the symmetric activation quantizer, otherwise the asymmetric one
 int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g,
-                           uint16_t* xh, uint8_t* xl, uint16_t* sx, hipStream_t s);
-int launch_w4a4_gemm(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const void* blob,
-                     const uint16_t* bias, int M, int N, int K, int r, int g, void* y, int y_dtype,
-                     hipStream_t s);
+                           uint16_t* xh, uint8_t* xl, uint16_t* sx, uint16_t* zx, hipStream_t s);
+int launch_w4a4_gemm(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const uint16_t* zx,
+                     const void* blob, const uint16_t* bias, int M, int N, int K, int r, int g, void* y,
+                     int y_dtype, hipStream_t s);
 int launch_prepare_rotation(const float* Q, int K, uint16_t* Qt, hipStream_t s);
 int launch_prepare_weights(const float* W, const float* Q, int N, int K, int r, int g, void* blob,
                            float* scratch, hipStream_t s);
@@ -109,6 +114,25 @@ __device__ __forceinline__ int quant_code(float v, float inv) {
 // fp8 (E4M3) number q * 2^-9, which is how the GEMM kernel feeds codes to the matrix pipe.
 __device__ __forceinline__ uint32_t code_nibble(int q) { return (uint32_t)(q < 0 ? (8 - q) : q) & 15u; }
 __device__ __forceinline__ uint32_t quant_nibble(float v, float inv) { return code_nibble(quant_code(v, inv)); }
+// Asymmetric form of the same quantizer (q_min = 0, q_max = 15): stored zero-point
+// fp16_rne(clamp(min, +-65504)) and stored scale fp16_rne(min((max - min) / 15, 65504)).
+__device__ __forceinline__ float group_zero(float mn, uint16_t& bits) {
+  _Float16 h = (_Float16)fminf(fmaxf(mn, -65504.0f), 65504.0f);
+  bits = __builtin_bit_cast(uint16_t, h);
+  return (float)h;
+}
+__device__ __forceinline__ float group_scale_asym(float mn, float mx, uint16_t& bits) {
+  float s32 = fminf((mx - mn) / 15.0f, 65504.0f);
+  _Float16 h = (_Float16)s32;
+  bits = __builtin_bit_cast(uint16_t, h);
+  return (float)h;
+}
+// Unsigned 4-bit code of v: clip(rint((v - z) * inv), 0, 15); stored as the plain nibble.
+__device__ __forceinline__ uint32_t quant_nibble_asym(float v, float zf, float inv) {
+  float t = rintf((v - zf) * inv);
+  t = fminf(fmaxf(t, 0.0f), 15.0f);
+  return (uint32_t)(int)t;
+}
 __device__ __forceinline__ int nibble_code(uint32_t nib) { return (nib & 8u) ? -(int)(nib & 7u) : (int)(nib & 7u); }
 #endif
 

@@ -83,7 +83,8 @@ __global__ __launch_bounds__(256) void split_quantize_rows_kernel(const float* _
                                                                   int K, int r, int g,
                                                                   uint16_t* __restrict__ hi,
                                                                   uint8_t* __restrict__ codes,
-                                                                  uint16_t* __restrict__ scales) {
+                                                                  uint16_t* __restrict__ scales,
+                                                                  int16_t* __restrict__ wsum) {
   const long u = (long)blockIdx.x * blockDim.x + threadIdx.x;
   const long n_hi = (long)rows * (r / 32);
   const int G = (K - r) / g;
@@ -105,8 +106,13 @@ __global__ __launch_bounds__(256) void split_quantize_rows_kernel(const float* _
   const float inv = group_inv(sf);
   scales[(size_t)j * rows + row] = sbits;
   uint8_t* d = codes + (size_t)row * ((K - r) / 2) + j * (g / 2);
-  for (int p = 0; p < g; p += 2)
-    d[p / 2] = (uint8_t)(quant_nibble(s[p], inv) | (quant_nibble(s[p + 1], inv) << 4));
+  int sum = 0;
+  for (int p = 0; p < g; p += 2) {
+    const int q0 = quant_code(s[p], inv), q1 = quant_code(s[p + 1], inv);
+    d[p / 2] = (uint8_t)(code_nibble(q0) | (code_nibble(q1) << 4));
+    sum += q0 + q1;
+  }
+  wsum[(size_t)j * rows + row] = (int16_t)sum;     // |sum| <= 7 * 128
 }
 
 int launch_prepare_weights(const float* W, const float* Q, int N, int K, int r, int g, void* blob,
@@ -118,7 +124,7 @@ int launch_prepare_weights(const float* W, const float* Q, int N, int K, int r, 
   const long units = (long)N * (r / 32) + (long)N * ((K - r) / g);
   hipLaunchKernelGGL(split_quantize_rows_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, s,
                      scratch, N, K, r, g, (uint16_t*)(bp + L.off_wh), (uint8_t*)(bp + L.off_codes),
-                     (uint16_t*)(bp + L.off_sw));
+                     (uint16_t*)(bp + L.off_sw), (int16_t*)(bp + L.off_wsum));
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? DIROTQ_OK : hip_failed(e);
 }
@@ -128,7 +134,8 @@ __global__ __launch_bounds__(256) void import_kernel(const uint16_t* __restrict_
                                                      const int8_t* __restrict__ codes,
                                                      const uint16_t* __restrict__ sw, int N, int K, int r,
                                                      int g, uint16_t* __restrict__ bwh,
-                                                     uint8_t* __restrict__ bq, uint16_t* __restrict__ bsw) {
+                                                     uint8_t* __restrict__ bq, uint16_t* __restrict__ bsw,
+                                                     int16_t* __restrict__ bwsum) {
   const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   const long n_wh = (long)N * r, n_q = (long)N * (K - r) / 2;
   const int G = (K - r) / g;
@@ -137,6 +144,10 @@ __global__ __launch_bounds__(256) void import_kernel(const uint16_t* __restrict_
   if (i < (long)N * G) {
     const int n = (int)(i / G), j = (int)(i % G);
     bsw[(size_t)j * N + n] = sw[i];
+    const int8_t* c = codes + (size_t)n * (K - r) + (size_t)j * g;
+    int sum = 0;
+    for (int p = 0; p < g; p++) sum += c[p];
+    bwsum[(size_t)j * N + n] = (int16_t)sum;
   }
 }
 
@@ -170,7 +181,7 @@ int launch_import_weights(const uint16_t* Wh, const int8_t* codes, const uint16_
   if (n == 0) return DIROTQ_OK;
   hipLaunchKernelGGL(import_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, Wh, codes, sw, N, K,
                      r, g, (uint16_t*)(bp + L.off_wh), (uint8_t*)(bp + L.off_codes),
-                     (uint16_t*)(bp + L.off_sw));
+                     (uint16_t*)(bp + L.off_sw), (int16_t*)(bp + L.off_wsum));
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? DIROTQ_OK : hip_failed(e);
 }

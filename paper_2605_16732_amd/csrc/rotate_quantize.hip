@@ -50,11 +50,13 @@ struct RQ {
   __device__ static __forceinline__ int swz(int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
 };
 
-template <int WGC, int WGT, int BK, int MI>
+// ASYM: asymmetric activation quantizer (zero-point min, 16 unsigned levels) instead of the
+// symmetric one; zx receives the zero-points, laid out like sx.
+template <int WGC, int WGT, int BK, int MI, bool ASYM>
 __global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK>::WAVES_PER_SIMD)) void rotate_quantize_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ Qt, int M, int K, int r, int g,
-    uint16_t* __restrict__ xh, uint8_t* __restrict__ xl, uint16_t* __restrict__ sx, int r_pad, int Kv, int n_ct,
-    int n_tt, int per_xcd, int sx_ld) {
+    uint16_t* __restrict__ xh, uint8_t* __restrict__ xl, uint16_t* __restrict__ sx, uint16_t* __restrict__ zx,
+    int r_pad, int Kv, int n_ct, int n_tt, int per_xcd, int sx_ld) {
   using C = RQ<WGC, WGT, BK>;
   extern __shared__ __align__(16) unsigned char smem[];
 
@@ -206,37 +208,61 @@ __global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK>::WAVES_PER_SIMD)) 
 #pragma unroll
     for (int j = 0; j < WT; j++) {
       const int m = m0 + wt * C::WAVE_T + j * 32 + (l & 31);
-      // absmax of each 32-channel tile over the lane pair, then combined per group
-      float tmax[4];
+      // absmax (symmetric) or min and max (asymmetric) of each 32-channel tile over the lane
+      // pair, then combined per group
+      float tmax[4], tmin[4];
 #pragma unroll
       for (int i = 0; i < 4; i++) {
-        float a = 0.0f;
+        if constexpr (ASYM) {
+          float lo = acc[i][j][0], hi = acc[i][j][0];
 #pragma unroll
-        for (int v = 0; v < 16; v++) a = fmaxf(a, fabsf(acc[i][j][v]));
-        tmax[i] = fmaxf(a, __shfl_xor(a, 32));
+          for (int v = 1; v < 16; v++) {
+            lo = fminf(lo, acc[i][j][v]);
+            hi = fmaxf(hi, acc[i][j][v]);
+          }
+          tmin[i] = fminf(lo, __shfl_xor(lo, 32));
+          tmax[i] = fmaxf(hi, __shfl_xor(hi, 32));
+        } else {
+          float a = 0.0f;
+#pragma unroll
+          for (int v = 0; v < 16; v++) a = fmaxf(a, fabsf(acc[i][j][v]));
+          tmax[i] = fmaxf(a, __shfl_xor(a, 32));
+          tmin[i] = 0.0f;
+        }
       }
       if (gi_tiles == 2) {
         tmax[0] = tmax[1] = fmaxf(tmax[0], tmax[1]);
         tmax[2] = tmax[3] = fmaxf(tmax[2], tmax[3]);
+        tmin[0] = tmin[1] = fminf(tmin[0], tmin[1]);
+        tmin[2] = tmin[3] = fminf(tmin[2], tmin[3]);
       } else if (gi_tiles == 4) {
         tmax[0] = tmax[1] = tmax[2] = tmax[3] = fmaxf(fmaxf(tmax[0], tmax[1]), fmaxf(tmax[2], tmax[3]));
+        tmin[0] = tmin[1] = tmin[2] = tmin[3] = fminf(fminf(tmin[0], tmin[1]), fminf(tmin[2], tmin[3]));
       }
 #pragma unroll
       for (int i = 0; i < 4; i++) {
         const int cl = cl0 + i * 32;                          // first 4-bit channel of this tile
         const bool valid = cl < KL && m < M;
-        uint16_t sbits;
-        const float sf = group_scale(tmax[i], sbits);
+        uint16_t sbits, zbits = 0;
+        float sf, zf = 0.0f;
+        if constexpr (ASYM) {
+          zf = group_zero(tmin[i], zbits);
+          sf = group_scale_asym(tmin[i], tmax[i], sbits);
+        } else {
+          sf = group_scale(tmax[i], sbits);
+        }
         const float inv = group_inv(sf);
-        if (valid && h == 0 && (i % gi_tiles) == 0) sx[(size_t)(cl / g) * sx_ld + m] = sbits;
+        if (valid && h == 0 && (i % gi_tiles) == 0) {
+          sx[(size_t)(cl / g) * sx_ld + m] = sbits;
+          if constexpr (ASYM) zx[(size_t)(cl / g) * sx_ld + m] = zbits;
+        }
+        auto nib = [&](float v) { return ASYM ? quant_nibble_asym(v, zf, inv) : quant_nibble(v, inv); };
         // this lane's 16 codes: quad q covers channels cl + 8q + 4h .. +3 -> one 16-bit piece
         uint32_t piece[4];
 #pragma unroll
         for (int q = 0; q < 4; q++) {
-          piece[q] = quant_nibble(acc[i][j][4 * q], inv) |
-                     quant_nibble(acc[i][j][4 * q + 1], inv) << 4 |
-                     quant_nibble(acc[i][j][4 * q + 2], inv) << 8 |
-                     quant_nibble(acc[i][j][4 * q + 3], inv) << 12;
+          piece[q] = nib(acc[i][j][4 * q]) | nib(acc[i][j][4 * q + 1]) << 4 | nib(acc[i][j][4 * q + 2]) << 8 |
+                     nib(acc[i][j][4 * q + 3]) << 12;
         }
         const uint32_t P0 = piece[0] | (piece[1] << 16), P1 = piece[2] | (piece[3] << 16);
         // lane h=0 keeps dwords 0,1 of the tile's 16 bytes, lane h=1 dwords 2,3
@@ -357,44 +383,86 @@ __global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK>::WAVES_PER_SIMD)) 
 #pragma unroll
     for (int j = 0; j < NJ; j++) {
       const int m = m0 + wt * 64 + j * 16 + lr;
-      // absmax per 32-channel unit (two tiles) in-lane; after the transpose row q holds unit q's
-      // four partial maxima, so row q finishes unit q
-      uint32_t um[4];
+      // absmax (symmetric) or min and max (asymmetric) per 32-channel unit (two tiles) in-lane;
+      // after the transpose row q holds unit q's four partial results, so row q finishes unit q
+      uint32_t um[4], un[4];
 #pragma unroll
       for (int u = 0; u < 4; u++) {
-        float v = 0.0f;
+        if constexpr (ASYM) {
+          float lo = acc[2 * u][j][0], hi = acc[2 * u][j][0];
 #pragma unroll
-        for (int e = 0; e < 4; e++) v = fmaxf(v, fmaxf(fabsf(acc[2 * u][j][e]), fabsf(acc[2 * u + 1][j][e])));
-        um[u] = __builtin_bit_cast(uint32_t, v);
-      }
-      transpose4(um);
-      float gm = fmaxf(fmaxf(__builtin_bit_cast(float, um[0]), __builtin_bit_cast(float, um[1])),
-                       fmaxf(__builtin_bit_cast(float, um[2]), __builtin_bit_cast(float, um[3])));
-      if (gu > 1) {                                           // groups of 2 or 4 units: combine rows
-        uint32_t e0 = __builtin_bit_cast(uint32_t, gm), e1 = e0;
-        swap16(e0, e1);                                       // e0 = rows (0,0,2,2), e1 = rows (1,1,3,3)
-        gm = fmaxf(__builtin_bit_cast(float, e0), __builtin_bit_cast(float, e1));
-        if (gu > 2) {
-          uint32_t f0 = __builtin_bit_cast(uint32_t, gm), f1 = f0;
-          swap32(f0, f1);                                     // f0 = rows (0,1,0,1), f1 = rows (2,3,2,3)
-          gm = fmaxf(__builtin_bit_cast(float, f0), __builtin_bit_cast(float, f1));
+          for (int e = 0; e < 4; e++) {
+            lo = fminf(lo, fminf(acc[2 * u][j][e], acc[2 * u + 1][j][e]));
+            hi = fmaxf(hi, fmaxf(acc[2 * u][j][e], acc[2 * u + 1][j][e]));
+          }
+          um[u] = __builtin_bit_cast(uint32_t, hi);
+          un[u] = __builtin_bit_cast(uint32_t, lo);
+        } else {
+          float v = 0.0f;
+#pragma unroll
+          for (int e = 0; e < 4; e++) v = fmaxf(v, fmaxf(fabsf(acc[2 * u][j][e]), fabsf(acc[2 * u + 1][j][e])));
+          um[u] = __builtin_bit_cast(uint32_t, v);
         }
       }
-      // row q: scale of the group that unit q belongs to
-      uint16_t sbits;
-      const float sf = group_scale(gm, sbits);
+      auto f = [](uint32_t b) { return __builtin_bit_cast(float, b); };
+      auto bits = [](float v) { return __builtin_bit_cast(uint32_t, v); };
+      transpose4(um);
+      float gm = fmaxf(fmaxf(f(um[0]), f(um[1])), fmaxf(f(um[2]), f(um[3]))), gn = 0.0f;
+      if constexpr (ASYM) {
+        transpose4(un);
+        gn = fminf(fminf(f(un[0]), f(un[1])), fminf(f(un[2]), f(un[3])));
+      }
+      if (gu > 1) {                                           // groups of 2 or 4 units: combine rows
+        uint32_t e0 = bits(gm), e1 = e0;
+        swap16(e0, e1);                                       // e0 = rows (0,0,2,2), e1 = rows (1,1,3,3)
+        gm = fmaxf(f(e0), f(e1));
+        if constexpr (ASYM) {
+          uint32_t d0 = bits(gn), d1 = d0;
+          swap16(d0, d1);
+          gn = fminf(f(d0), f(d1));
+        }
+        if (gu > 2) {
+          uint32_t f0 = bits(gm), f1 = f0;
+          swap32(f0, f1);                                     // f0 = rows (0,1,0,1), f1 = rows (2,3,2,3)
+          gm = fmaxf(f(f0), f(f1));
+          if constexpr (ASYM) {
+            uint32_t c0 = bits(gn), c1 = c0;
+            swap32(c0, c1);
+            gn = fminf(f(c0), f(c1));
+          }
+        }
+      }
+      // row q: scale (and zero-point) of the group that unit q belongs to
+      uint16_t sbits, zbits = 0;
+      float sf, zf_q = 0.0f;
+      if constexpr (ASYM) {
+        zf_q = group_zero(gn, zbits);
+        sf = group_scale_asym(gn, gm, sbits);
+      } else {
+        sf = group_scale(gm, sbits);
+      }
       const float inv_q = group_inv(sf);
       const int clu = cl0 + 32 * hq;                          // first channel of unit hq
       const bool valid = clu < KL && m < M;
-      if (valid && (hq % gu) == 0) sx[(size_t)(clu / g) * sx_ld + m] = sbits;
-      // broadcast the four reciprocals to all rows
-      uint32_t i0 = __builtin_bit_cast(uint32_t, inv_q), i1 = i0;
-      swap16(i0, i1);                                         // i0 = rows (0,0,2,2), i1 = rows (1,1,3,3)
-      uint32_t i2 = i0, i3 = i1;
-      swap32(i0, i2);                                         // i0 = row 0 everywhere, i2 = row 2 everywhere
-      swap32(i1, i3);                                         // i1 = row 1 everywhere, i3 = row 3 everywhere
-      const float inv[4] = {__builtin_bit_cast(float, i0), __builtin_bit_cast(float, i1),
-                            __builtin_bit_cast(float, i2), __builtin_bit_cast(float, i3)};
+      if (valid && (hq % gu) == 0) {
+        sx[(size_t)(clu / g) * sx_ld + m] = sbits;
+        if constexpr (ASYM) zx[(size_t)(clu / g) * sx_ld + m] = zbits;
+      }
+      // broadcast the four rows' values to all rows: b[u] = row u's value everywhere
+      auto broadcast4 = [&](float v, float (&b)[4]) {
+        uint32_t i0 = bits(v), i1 = i0;
+        swap16(i0, i1);                                       // i0 = rows (0,0,2,2), i1 = rows (1,1,3,3)
+        uint32_t i2 = i0, i3 = i1;
+        swap32(i0, i2);                                       // i0 = row 0 everywhere, i2 = row 2 everywhere
+        swap32(i1, i3);                                       // i1 = row 1 everywhere, i3 = row 3 everywhere
+        b[0] = f(i0);
+        b[1] = f(i1);
+        b[2] = f(i2);
+        b[3] = f(i3);
+      };
+      float inv[4], zf[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      broadcast4(inv_q, inv);
+      if constexpr (ASYM) broadcast4(zf_q, zf);
       // codes: P[u] = the lane's 4 + 4 codes of unit u (tile 2u in the low half, tile 2u+1 in the high half)
       uint32_t P[4];
 #pragma unroll
@@ -404,7 +472,9 @@ __global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK>::WAVES_PER_SIMD)) 
         for (int half = 0; half < 2; half++)
 #pragma unroll
           for (int e = 0; e < 4; e++)
-            pc |= quant_nibble(acc[2 * u + half][j][e], inv[u]) << (16 * half + 4 * e);
+            pc |= (ASYM ? quant_nibble_asym(acc[2 * u + half][j][e], zf[u], inv[u])
+                        : quant_nibble(acc[2 * u + half][j][e], inv[u]))
+                  << (16 * half + 4 * e);
         P[u] = pc;
       }
       transpose4(P);                                          // P[h] = row h's codes of unit hq
@@ -419,15 +489,16 @@ __global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK>::WAVES_PER_SIMD)) 
   }
 }
 
-template <int WGC, int WGT, int BK, int MI>
-static int launch_cfg(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g, uint16_t* xh,
-                      uint8_t* xl, uint16_t* sx, hipStream_t s, int m_off = 0, int sx_ld = 0) {
+template <int WGC, int WGT, int BK, int MI, bool ASYM>
+static int launch_one(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g, uint16_t* xh,
+                      uint8_t* xl, uint16_t* sx, uint16_t* zx, hipStream_t s, int m_off, int sx_ld) {
   // tokens [m_off, m_off + M) of the caller's arrays; sx_ld = total token count (row length of s_x)
   if (sx_ld == 0) sx_ld = M;
   x += (size_t)m_off * K;
   if (xh) xh += (size_t)m_off * r;
   if (xl) xl += (size_t)m_off * ((K - r) / 2);
   if (sx) sx += m_off;
+  if (zx) zx += m_off;
   using C = RQ<WGC, WGT, BK>;
   const int r_pad = (r + 127) / 128 * 128;
   const int Kv = r_pad + (K - r + 127) / 128 * 128;
@@ -437,19 +508,26 @@ static int launch_cfg(const uint16_t* x, const uint16_t* Qt, int M, int K, int r
   const int per_xcd = (int)((n_blocks + 7) / 8);
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)rotate_quantize_kernel<WGC, WGT, BK, MI>,
+    hipError_t e = hipFuncSetAttribute((const void*)rotate_quantize_kernel<WGC, WGT, BK, MI, ASYM>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
     if (e != hipSuccess) return hip_failed(e);
     attr_done = true;
   }
-  hipLaunchKernelGGL((rotate_quantize_kernel<WGC, WGT, BK, MI>), dim3(per_xcd * 8), dim3(C::NT), C::SMEM, s, x,
-                     Qt, M, K, r, g, xh, xl, sx, r_pad, Kv, n_ct, n_tt, per_xcd, sx_ld);
+  hipLaunchKernelGGL((rotate_quantize_kernel<WGC, WGT, BK, MI, ASYM>), dim3(per_xcd * 8), dim3(C::NT), C::SMEM, s, x,
+                     Qt, M, K, r, g, xh, xl, sx, zx, r_pad, Kv, n_ct, n_tt, per_xcd, sx_ld);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? DIROTQ_OK : hip_failed(e);
 }
 
+template <int WGC, int WGT, int BK, int MI>
+static int launch_cfg(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g, uint16_t* xh,
+                      uint8_t* xl, uint16_t* sx, uint16_t* zx, hipStream_t s, int m_off = 0, int sx_ld = 0) {
+  return zx ? launch_one<WGC, WGT, BK, MI, true>(x, Qt, M, K, r, g, xh, xl, sx, zx, s, m_off, sx_ld)
+            : launch_one<WGC, WGT, BK, MI, false>(x, Qt, M, K, r, g, xh, xl, sx, zx, s, m_off, sx_ld);
+}
+
 int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g, uint16_t* xh,
-                           uint8_t* xl, uint16_t* sx, hipStream_t s) {
+                           uint8_t* xl, uint16_t* sx, uint16_t* zx, hipStream_t s) {
   // Large problems: 256 x 256 workgroup tiles (8 waves); medium: 256 channels x 128 tokens
   // (4 waves); small: 128 x 128 (2 waves), so that the grid still covers the chip.
   // The large tiles run long enough to be limited by power (the shader clock drops under
@@ -462,11 +540,11 @@ int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, 
   const long big_tiles = n_tc256 * ((M + 255) / 256);    // 256 channels x 256 tokens
   const long mid_tiles = n_tc256 * ((M + 127) / 128);    // 256 channels x 128 tokens
 #ifdef DIROTQ_RQ_FORCE   // build-time tuning aid: -DDIROTQ_RQ_FORCE=WGC,WGT,BK,MI (K % BK must be 0)
-  return launch_cfg<DIROTQ_RQ_FORCE>(x, Qt, M, K, r, g, xh, xl, sx, s);
+  return launch_cfg<DIROTQ_RQ_FORCE>(x, Qt, M, K, r, g, xh, xl, sx, zx, s);
 #endif
   if (K % 64 != 0) {
-    if (mid_tiles >= 100) return launch_cfg<2, 2, 32, 32>(x, Qt, M, K, r, g, xh, xl, sx, s);
-    return launch_cfg<1, 2, 32, 32>(x, Qt, M, K, r, g, xh, xl, sx, s);
+    if (mid_tiles >= 100) return launch_cfg<2, 2, 32, 32>(x, Qt, M, K, r, g, xh, xl, sx, zx, s);
+    return launch_cfg<1, 2, 32, 32>(x, Qt, M, K, r, g, xh, xl, sx, zx, s);
   }
   if (big_tiles >= 200) {
     // 256 CUs take one big tile each per round.  When the last round would be less than ~40%
@@ -475,14 +553,14 @@ int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, 
     const long full = big_tiles / 256 * 256, tail = big_tiles - full;
     const int tt_big = (int)(full / n_tc256);               // token tiles covered by full rounds
     if (full > 0 && tail > 0 && tail <= 104 && tt_big * 256 < M && (M - tt_big * 256) % 128 == 0) {
-      int st = launch_cfg<2, 4, 64, 16>(x, Qt, tt_big * 256, K, r, g, xh, xl, sx, s, 0, M);
+      int st = launch_cfg<2, 4, 64, 16>(x, Qt, tt_big * 256, K, r, g, xh, xl, sx, zx, s, 0, M);
       if (st) return st;
-      return launch_cfg<2, 2, 64, 32>(x, Qt, M - tt_big * 256, K, r, g, xh, xl, sx, s, tt_big * 256, M);
+      return launch_cfg<2, 2, 64, 32>(x, Qt, M - tt_big * 256, K, r, g, xh, xl, sx, zx, s, tt_big * 256, M);
     }
-    return launch_cfg<2, 4, 64, 16>(x, Qt, M, K, r, g, xh, xl, sx, s);
+    return launch_cfg<2, 4, 64, 16>(x, Qt, M, K, r, g, xh, xl, sx, zx, s);
   }
-  if (mid_tiles >= 100) return launch_cfg<2, 2, 64, 32>(x, Qt, M, K, r, g, xh, xl, sx, s);
-  return launch_cfg<1, 2, 32, 32>(x, Qt, M, K, r, g, xh, xl, sx, s);
+  if (mid_tiles >= 100) return launch_cfg<2, 2, 64, 32>(x, Qt, M, K, r, g, xh, xl, sx, zx, s);
+  return launch_cfg<1, 2, 32, 32>(x, Qt, M, K, r, g, xh, xl, sx, zx, s);
 }
 
 }  // namespace dirotq

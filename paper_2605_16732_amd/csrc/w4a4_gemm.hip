@@ -23,6 +23,13 @@
 // common factor 2^18 is applied once at the end (exact), before the 16-bit branch is
 // accumulated on top by bf16 MFMAs.
 //
+// Asymmetric activations (ASYM).  Codes are then unsigned nibbles, whose zero-extended byte
+// is again an exact fp8 number (u * 2^-9 for u in 0..15: the first binade continues the
+// subnormals linearly), so the main loop is unchanged.  The zero-point term
+// sum_j z[m,j] * (s_w[n,j] * sum_k q_w[n,k]) is a small GEMM over the groups; it is added
+// after the main loop by bf16 MFMAs on exact bf16 splits of its factors (z = z1 + z2,
+// c = b1 + b2 + b3; every product but z2 b3, which is below 2^-24 of the term, is kept).
+//
 // Schedule.  The vector ALU is the binding unit (one fma per accumulator and group plus the
 // unpacking, against 64 cycles of fp8 MFMA per tile and 64-channel group), so the main loop
 // is software-pipelined by hand: the MFMAs of tile s+1 are issued before the fma sweep of
@@ -65,12 +72,18 @@ __device__ __forceinline__ f32x16 mfma_fp8_k64(i32x4 a_lo, i32x4 a_hi, i32x4 b_l
   return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);
 }
 
-template <int GS, bool OUT_F32>
+// 8 unsigned nibbles of a dword -> two dwords of fp8 bytes 0000uuuu = u * 2^-9
+__device__ __forceinline__ void unpack8u(uint32_t p, uint32_t& even, uint32_t& odd) {
+  even = p & 0x0F0F0F0Fu;
+  odd = (p >> 4) & 0x0F0F0F0Fu;
+}
+
+template <int GS, bool OUT_F32, bool ASYM>
 __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
     const uint16_t* __restrict__ xh, const uint8_t* __restrict__ xl, const uint16_t* __restrict__ sx,
-    const uint16_t* __restrict__ wh, const uint8_t* __restrict__ wq, const uint16_t* __restrict__ sw,
-    const uint16_t* __restrict__ bias, int M, int N, int K, int r, void* __restrict__ y, int n_mt, int n_nt,
-    int per_xcd) {
+    const uint16_t* __restrict__ zx, const uint16_t* __restrict__ wh, const uint8_t* __restrict__ wq,
+    const uint16_t* __restrict__ sw, const int16_t* __restrict__ wsum, const uint16_t* __restrict__ bias, int M,
+    int N, int K, int r, void* __restrict__ y, int n_mt, int n_nt, int per_xcd) {
   extern __shared__ __align__(16) unsigned char smem[];
 
   const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
@@ -153,10 +166,17 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
       if (i < 4) {
         const int row = prow + 64 * i;
         uint4 e, o;
-        unpack8(rq[i].x, e.x, o.x);
-        unpack8(rq[i].y, e.y, o.y);
-        unpack8(rq[i].z, e.z, o.z);
-        unpack8(rq[i].w, e.w, o.w);
+        if (ASYM && i >= 2) {                 // rows 128..255 of a stage are tokens: unsigned codes
+          unpack8u(rq[i].x, e.x, o.x);
+          unpack8u(rq[i].y, e.y, o.y);
+          unpack8u(rq[i].z, e.z, o.z);
+          unpack8u(rq[i].w, e.w, o.w);
+        } else {
+          unpack8(rq[i].x, e.x, o.x);
+          unpack8(rq[i].y, e.y, o.y);
+          unpack8(rq[i].z, e.z, o.z);
+          unpack8(rq[i].w, e.w, o.w);
+        }
         *(uint4*)(sb + tile_off_bytes(row, 2 * pchunk)) = e;
         *(uint4*)(sb + tile_off_bytes(row, 2 * pchunk + 1)) = o;
       } else {
@@ -299,6 +319,97 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
       for (int j = 0; j < 2; j++)
 #pragma unroll
         for (int v = 0; v < 16; v++) acc[i][j][v] *= 262144.0f;
+
+    // ---- zero-point term of asymmetric activations: acc += sum_j z[m,j] c[n,j], c = s_w * sum_k q_w
+    if constexpr (ASYM) {
+      // 12 groups per pass: thread t fills row t of a [256 rows][64 bf16] tile, 5 k-slots per group:
+      // weight rows b1 b2 b3 b1 b2, token rows z1 z1 z1 z2 z2 (group-major sources: coalesced over
+      // rows).  z = z1 + z2 and c = b1 + b2 + b3 exactly; only z2 b3 (< 2^-24 of the term) is dropped.
+      constexpr int GPP = 12;
+      const bool is_w = t < TN;                             // uniform per wave
+      const size_t ld = is_w ? (size_t)N : (size_t)M;
+      const size_t col = is_w ? (size_t)min(n0 + t, N - 1) : (size_t)min(m0 + t - TN, M - 1);
+      // Raw factors are fetched two passes ahead (a pass is much shorter than a load's latency).
+      // Loads only here, straight-line per wave: the arithmetic on them waits until they are used.
+      uint32_t ra[2][GPP];                                  // s_w bits, or z bits
+      int rb[2][GPP];                                       // code sums (weight rows only)
+      // (token rows read their z twice rather than branch: no control flow between the loads)
+      const uint16_t* src_a = is_w ? sw : zx;
+      const int16_t* src_b = is_w ? wsum : (const int16_t*)zx;
+      auto fetch = [&](int u, int j0) {
+#pragma unroll
+        for (int gg = 0; gg < GPP; gg++) {
+          const size_t idx = (size_t)min(j0 + gg, G - 1) * ld + col;
+          ra[u][gg] = src_a[idx];
+          rb[u][gg] = src_b[idx];
+        }
+      };
+      // v = p1 + p2 + p3 with each piece a bf16 number: truncating splits (exact, the residuals
+      // need no rounding); a piece is kept as fp32 bits with the low half clear
+      auto hi16 = [](float v) { return __builtin_bit_cast(uint32_t, v) & 0xFFFF0000u; };
+      auto pair = [](uint32_t lo, uint32_t hi) { return (lo >> 16) | hi; };   // two bf16 slots in a dword
+      auto pass = [&](int u, int j0) {
+        uint32_t slot[64];                                  // fp32-bit pieces, one per k-slot
+#pragma unroll
+        for (int k = 60; k < 64; k++) slot[k] = 0;
+        if (is_w) {
+#pragma unroll
+          for (int gg = 0; gg < GPP; gg++) {
+            const float v = j0 + gg < G ? f16_bits_to_f32((uint16_t)ra[u][gg]) * (float)rb[u][gg] : 0.0f;
+            const uint32_t p1 = hi16(v);
+            const float r1 = v - __builtin_bit_cast(float, p1);
+            const uint32_t p2 = hi16(r1);
+            const uint32_t p3 = hi16(r1 - __builtin_bit_cast(float, p2));
+            slot[5 * gg + 0] = p1;
+            slot[5 * gg + 1] = p2;
+            slot[5 * gg + 2] = p3;
+            slot[5 * gg + 3] = p1;
+            slot[5 * gg + 4] = p2;
+          }
+        } else {
+#pragma unroll
+          for (int gg = 0; gg < GPP; gg++) {
+            const float v = j0 + gg < G ? f16_bits_to_f32((uint16_t)ra[u][gg]) : 0.0f;   // an fp16 value: two pieces hold it
+            const uint32_t p1 = hi16(v);
+            const uint32_t p2 = hi16(v - __builtin_bit_cast(float, p1));
+            slot[5 * gg + 0] = p1;
+            slot[5 * gg + 1] = p1;
+            slot[5 * gg + 2] = p1;
+            slot[5 * gg + 3] = p2;
+            slot[5 * gg + 4] = p2;
+          }
+        }
+        fetch(u, j0 + 2 * GPP);                             // past the end: clamped, never used
+        __syncthreads();                                    // the previous use of this LDS tile is over
+#pragma unroll
+        for (int c8 = 0; c8 < 8; c8++)
+          *(uint4*)(smem + tile_off_bytes(t, c8)) =
+              make_uint4(pair(slot[8 * c8], slot[8 * c8 + 1]), pair(slot[8 * c8 + 2], slot[8 * c8 + 3]),
+                         pair(slot[8 * c8 + 4], slot[8 * c8 + 5]), pair(slot[8 * c8 + 6], slot[8 * c8 + 7]));
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) {
+          bf16x8 a[2], b[2];
+          const int chunk = 2 * ks + h;
+#pragma unroll
+          for (int i = 0; i < 2; i++) a[i] = *(const bf16x8*)(smem + rowA[i] * 128 + ((chunk ^ swz) << 4));
+#pragma unroll
+          for (int j = 0; j < 2; j++) b[j] = *(const bf16x8*)(smem + rowB[j] * 128 + ((chunk ^ swz) << 4));
+#pragma unroll
+          for (int i = 0; i < 2; i++)
+#pragma unroll
+            for (int j = 0; j < 2; j++)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+      };
+      fetch(0, 0);
+      fetch(1, GPP);
+      for (int j0 = 0; j0 < G; j0 += 2 * GPP) {
+#pragma unroll
+        for (int u = 0; u < 2; u++)
+          if (j0 + u * GPP < G) pass(u, j0 + u * GPP);
+      }
+    }
   }
 
   // ---- 16-bit branch: acc += W'_h x_h^T, bf16 MFMA, 64 channels per pass ----------
@@ -386,9 +497,10 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
   }
 }
 
-template <int GS, bool OUT_F32>
-static int launch_one(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const void* blob,
-                      const uint16_t* bias, int M, int N, int K, int r, void* y, hipStream_t s) {
+template <int GS, bool OUT_F32, bool ASYM>
+static int launch_one(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const uint16_t* zx,
+                      const void* blob, const uint16_t* bias, int M, int N, int K, int r, void* y,
+                      hipStream_t s) {
   const BlobLayout L = blob_layout(N, K, r, GS);
   const char* bp = (const char*)blob;
   const int n_mt = (M + TM - 1) / TM, n_nt = (N + TN - 1) / TN;
@@ -396,25 +508,29 @@ static int launch_one(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx,
   const int per_xcd = (int)((n_blocks + 7) / 8);
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)w4a4_gemm_kernel<GS, OUT_F32>,
+    hipError_t e = hipFuncSetAttribute((const void*)w4a4_gemm_kernel<GS, OUT_F32, ASYM>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes(GS));
     if (e != hipSuccess) return hip_failed(e);
     attr_done = true;
   }
-  hipLaunchKernelGGL((w4a4_gemm_kernel<GS, OUT_F32>), dim3(per_xcd * 8), dim3(NTHREADS), smem_bytes(GS), s, xh,
-                     xl, sx, (const uint16_t*)(bp + L.off_wh), (const uint8_t*)(bp + L.off_codes),
-                     (const uint16_t*)(bp + L.off_sw), bias, M, N, K, r, y, n_mt, n_nt, per_xcd);
+  hipLaunchKernelGGL((w4a4_gemm_kernel<GS, OUT_F32, ASYM>), dim3(per_xcd * 8), dim3(NTHREADS), smem_bytes(GS), s, xh,
+                     xl, sx, zx, (const uint16_t*)(bp + L.off_wh), (const uint8_t*)(bp + L.off_codes),
+                     (const uint16_t*)(bp + L.off_sw), (const int16_t*)(bp + L.off_wsum), bias, M, N, K, r, y,
+                     n_mt, n_nt, per_xcd);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? DIROTQ_OK : hip_failed(e);
 }
 
-int launch_w4a4_gemm(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const void* blob,
-                     const uint16_t* bias, int M, int N, int K, int r, int g, void* y, int y_dtype,
-                     hipStream_t s) {
-#define DIROTQ_CASE(GS)                                                                        \
-  case GS:                                                                                     \
-    return y_dtype ? launch_one<GS, true>(xh, xl, sx, blob, bias, M, N, K, r, y, s)            \
-                   : launch_one<GS, false>(xh, xl, sx, blob, bias, M, N, K, r, y, s);
+int launch_w4a4_gemm(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const uint16_t* zx,
+                     const void* blob, const uint16_t* bias, int M, int N, int K, int r, int g, void* y,
+                     int y_dtype, hipStream_t s) {
+#define DIROTQ_CASE(GS)                                                                               \
+  case GS:                                                                                            \
+    if (zx)                                                                                           \
+      return y_dtype ? launch_one<GS, true, true>(xh, xl, sx, zx, blob, bias, M, N, K, r, y, s)       \
+                     : launch_one<GS, false, true>(xh, xl, sx, zx, blob, bias, M, N, K, r, y, s);     \
+    return y_dtype ? launch_one<GS, true, false>(xh, xl, sx, zx, blob, bias, M, N, K, r, y, s)        \
+                   : launch_one<GS, false, false>(xh, xl, sx, zx, blob, bias, M, N, K, r, y, s);
   switch (g) {
     DIROTQ_CASE(32)
     DIROTQ_CASE(64)
@@ -425,3 +541,4 @@ int launch_w4a4_gemm(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, 
 }
 
 }  // namespace dirotq
+

@@ -36,12 +36,13 @@ def test_strerror():
 
 
 def test_size_queries():
-    # blob: Wh bf16 [N,r] | packed codes [N,(K-r)/2] | fp16 scales [G,N], each section padded to 256 B
+    # blob: Wh bf16 [N,r] | packed codes [N,(K-r)/2] | fp16 scales [G,N] | i16 code sums [G,N];
+    # workspace: xh | xl | sx | zx; each section padded to 256 B
     N, K, r, g = 1152, 1152, 64, 64
     G = (K - r) // g
     pad = lambda v: (v + 255) // 256 * 256
-    assert B.weights_bytes(N, K, r, g) == pad(N * r * 2) + pad(N * (K - r) // 2) + pad(G * N * 2)
-    assert B.workspace_bytes(256, K, r, g) == pad(256 * r * 2) + pad(256 * (K - r) // 2) + pad(G * 256 * 2)
+    assert B.weights_bytes(N, K, r, g) == pad(N * r * 2) + pad(N * (K - r) // 2) + 2 * pad(G * N * 2)
+    assert B.workspace_bytes(256, K, r, g) == pad(256 * r * 2) + pad(256 * (K - r) // 2) + 2 * pad(G * 256 * 2)
     assert B.prepare_scratch_bytes(N, K) == N * K * 4
     assert B.workspace_bytes(0, K, r, g) >= 0
 
@@ -80,6 +81,16 @@ def test_argument_errors_before_any_launch():
     assert L.dirotq_prepare_rotation(a, 48, a, None) == B.ERR_SHAPE
     assert L.dirotq_import_weights(None, None, None, 8, 64, 0, 32, a, None) == B.ERR_NULL
     assert L.dirotq_export_weights(None, 8, 64, 0, 32, a, a, a, None) == B.ERR_NULL
+    # asymmetric-activation entry points: same rules, plus the zero-point array
+    assert L.dirotq_rotate_quantize_asym(a, a, 4, 64, 0, 32, None, a, a, None, None) == B.ERR_NULL       # zx needed
+    assert L.dirotq_rotate_quantize_asym(a, a, 4, 64, 0, 32, None, a, a, a + 2, None) == B.ERR_ALIGN
+    assert L.dirotq_rotate_quantize_asym(a, a, 4, 64, 0, 96, None, a, a, a, None) == B.ERR_SHAPE
+    assert L.dirotq_w4a4_gemm_asym(None, a, a, None, a, None, 4, 8, 64, 0, 32, a, 0, None) == B.ERR_NULL   # zx needed
+    assert L.dirotq_w4a4_gemm_asym(None, a, a, a, a, None, 4, 8, 64, 0, 32, a, 3, None) == B.ERR_UNSUPPORTED
+    assert L.dirotq_linear_asym(a, a, a, None, 4, 8, 64, 0, 32, a, a, 16, None) == B.ERR_WORKSPACE
+    assert L.dirotq_rotate_quantize_asym(a, a, 0, 64, 0, 32, None, a, a, a, None) == B.OK
+    assert L.dirotq_w4a4_gemm_asym(None, a, a, a, a, None, 0, 8, 64, 0, 32, a, 0, None) == B.OK
+    assert L.dirotq_linear_asym(a, a, a, None, 0, 8, 64, 0, 32, a, a, 0, None) == B.OK
     # M == 0 is a valid no-op and launches nothing
     assert L.dirotq_rotate_quantize(a, a, 0, 64, 0, 32, None, a, a, None) == B.OK
     assert L.dirotq_w4a4_gemm(None, a, a, a, None, 0, 8, 64, 0, 32, a, 0, None) == B.OK
