@@ -415,17 +415,29 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
   // ---- 16-bit branch: acc += W'_h x_h^T, bf16 MFMA, 64 channels per pass ----------
   if (r > 0) {
     const int lrow = t >> 3, lchunk = t & 7;   // 8 rows (stride 32) x one 16-B chunk per thread
+    const uint16_t* src[8];
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+      const int row = lrow + 32 * i;
+      src[i] = (row < TN ? wh + (size_t)min(n0 + row, N - 1) * r : xh + (size_t)min(m0 + row - TN, M - 1) * r) +
+               lchunk * 8;
+    }
+    // the next pass is loaded into registers while the current one is multiplied; channels past r
+    // re-read the row's last chunk and are zeroed (unconditional loads, no control flow between them)
+    uint4 v[8];
+    auto fetch = [&](int k0) {
+      const int off = min(k0 + lchunk * 8, r - 8) - lchunk * 8;
+#pragma unroll
+      for (int i = 0; i < 8; i++) v[i] = *(const uint4*)(src[i] + off);
+    };
+    fetch(0);
     for (int k0 = 0; k0 < r; k0 += 64) {
       const bool ok = k0 + lchunk * 8 < r;
       __syncthreads();
 #pragma unroll
-      for (int i = 0; i < 8; i++) {
-        const int row = lrow + 32 * i;
-        const uint16_t* src = row < TN ? wh + (size_t)min(n0 + row, N - 1) * r
-                                       : xh + (size_t)min(m0 + row - TN, M - 1) * r;
-        const uint4 v = ok ? *(const uint4*)(src + k0 + lchunk * 8) : make_uint4(0, 0, 0, 0);
-        *(uint4*)(smem + tile_off_bytes(row, lchunk)) = v;
-      }
+      for (int i = 0; i < 8; i++)
+        *(uint4*)(smem + tile_off_bytes(lrow + 32 * i, lchunk)) = ok ? v[i] : make_uint4(0, 0, 0, 0);
+      fetch(min(k0 + 64, r - 8));                // past the end: a harmless re-read, never used
       __syncthreads();
 #pragma unroll
       for (int ks = 0; ks < 4; ks++) {
