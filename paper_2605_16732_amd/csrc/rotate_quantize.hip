@@ -547,12 +547,13 @@ int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, 
     return launch_cfg<1, 2, 32, 32>(x, Qt, M, K, r, g, xh, xl, sx, zx, s);
   }
   if (big_tiles >= 200) {
-    // 256 CUs take one big tile each per round.  When the last round would be less than ~40%
+    // 256 CUs take one big tile each per round.  When the last round would be less than 40-60%
     // full, the tokens of that round are done with half-size tiles in a second launch instead,
     // so that they spread over the whole chip.
     const long full = big_tiles / 256 * 256, tail = big_tiles - full;
     const int tt_big = (int)(full / n_tc256);               // token tiles covered by full rounds
-    if (full > 0 && tail > 0 && tail <= 104 && tt_big * 256 < M && (M - tt_big * 256) % 128 == 0) {
+    const long tail_max = K >= 2048 ? 150 : 104;            // short tiles pay more for the second launch
+    if (full > 0 && tail > 0 && tail <= tail_max && tt_big * 256 < M && (M - tt_big * 256) % 128 == 0) {
       int st = launch_cfg<2, 4, 64, 16>(x, Qt, tt_big * 256, K, r, g, xh, xl, sx, zx, s, 0, M);
       if (st) return st;
       return launch_cfg<2, 2, 64, 32>(x, Qt, M - tt_big * 256, K, r, g, xh, xl, sx, zx, s, tt_big * 256, M);
