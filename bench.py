@@ -58,6 +58,9 @@ def main() -> int:
                          "(configs[3]); ablation = rank/group grid on the FLUX fc2 shape (configs[4])")
     ap.add_argument("--residual-rotation", action="store_true",
                     help="fold a random orthogonal rotation of the 4-bit subspace into Q (Q = [U_h, U_l R])")
+    ap.add_argument("--shared-input", action="store_true",
+                    help="flux only: fused QKV and fc1 read the same activations (as in FLUX's single-stream blocks): "
+                         "one dirotq_linear_shared call rotates and quantizes them once for both GEMMs")
     ap.add_argument("--asym", action="store_true",
                     help="asymmetric activation quantizer (zero-point min, 16 unsigned levels): the *_asym entry points")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -101,11 +104,17 @@ def main() -> int:
             blob = B.prepare_weights(W, Q32, shp.r, shp.g)
         else:
             L = I.make_layer(shp, residual_rotation=args.residual_rotation)
-            Q32 = torch.from_numpy(L.Q32).to(dev)
             W = torch.from_numpy(L.W).to(dev)
-            Qt = B.prepare_rotation(Q32)
+            if args.shared_input and shp.name == "flux_fc1":
+                # fc1 reads the QKV layer's activations through the QKV layer's rotation
+                L0 = layers[0]["host"]
+                Q32 = torch.from_numpy(L0.Q32).to(dev)
+                Qt, x = layers[0]["Qt"], layers[0]["x"]
+            else:
+                Q32 = torch.from_numpy(L.Q32).to(dev)
+                Qt = B.prepare_rotation(Q32)
+                x = dev_bf16(L.x_bits)
             blob = B.prepare_weights(W, Q32, shp.r, shp.g)
-            x = dev_bf16(L.x_bits)
             Wb = W.to(torch.bfloat16)                 # comparator: plain bf16 GEMM, same shape
             del Q32, W
         ws = torch.empty(B.workspace_bytes(shp.M, shp.K, shp.r, shp.g), dtype=torch.uint8, device=dev)
@@ -132,10 +141,21 @@ def main() -> int:
     f_rq = B.rotate_quantize_asym if args.asym else B.rotate_quantize
     f_gemm = B.w4a4_gemm_asym if args.asym else B.w4a4_gemm
 
+    if args.shared_input and (args.workload != "flux" or args.asym):
+        print("bench.py: --shared-input applies to the symmetric flux workload", file=sys.stderr)
+        return 2
+
     def step():
-        for Ld in layers:
+        for i, Ld in enumerate(layers):
             s = Ld["shape"]
-            f_linear(Ld["x"], Ld["Qt"], Ld["blob"], s.N, s.r, s.g, workspace=Ld["ws"], out=Ld["y"])
+            if args.shared_input and i == 0:
+                L2 = layers[2]
+                B.linear_shared(Ld["x"], Ld["Qt"], [Ld["blob"], L2["blob"]], [s.N, L2["shape"].N], s.r, s.g,
+                                workspace=Ld["ws"], outs=[Ld["y"], L2["y"]])
+            elif args.shared_input and i == 2:
+                continue
+            else:
+                f_linear(Ld["x"], Ld["Qt"], Ld["blob"], s.N, s.r, s.g, workspace=Ld["ws"], out=Ld["y"])
 
     # ---- whole-step timing -----------------------------------------------------------
     for _ in range(args.warmup):
@@ -274,7 +294,8 @@ def main() -> int:
                                 "sweep": "configs[3]: token sweep on the PixArt fc1 shape, M in {1024..32768}",
                                 "ablation": "configs[4]: rank/group grid on the FLUX fc2 shape"}[args.workload],
                    "seed": 0, "effective_ops_per_step": total_ops, "residual_rotation": args.residual_rotation,
-                   "activation_quantizer": "asymmetric" if args.asym else "symmetric"},
+                   "activation_quantizer": "asymmetric" if args.asym else "symmetric",
+                   "shared_input": bool(args.shared_input)},
         "speedup_vs_bf16_gemm": round(bf16_ms / ms_per_step, 4),
         "bf16_gemm_ms_per_step": round(bf16_ms, 4),
         "roofline": {k: (round(v, 5) if isinstance(v, float) else v) for k, v in roofline.items()},

@@ -147,6 +147,20 @@ int dirotq_linear(const uint16_t* x_bf16, const uint16_t* Qt_bf16, const void* b
                   const uint16_t* bias_bf16, int M, int N, int K, int r, int g,
                   uint16_t* y_bf16 /*out*/, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Several layers that read the same activations (fused QKV next to the MLP's first
+ * projection in a block whose branches share their input, Section 5.1's FLUX blocks):
+ * one dirotq_rotate_quantize into `workspace`, then one dirotq_w4a4_gemm per output.
+ * All outputs share K, r, g and the rotation; output i has N = Ns[i], weights blobs[i],
+ * bias biases[i] (the array or any entry may be NULL) and result ys[i] bf16 [M, Ns[i]].
+ * blobs, biases, Ns, ys are HOST arrays of n_out entries (1 <= n_out <= 16) holding
+ * device pointers.  Results are bit-identical to n_out dirotq_linear calls.
+ */
+int dirotq_linear_shared(const uint16_t* x_bf16, const uint16_t* Qt_bf16, int n_out,
+                         const void* const* blobs /*host*/, const uint16_t* const* biases /*host*/,
+                         const int* Ns /*host*/, uint16_t* const* ys /*host, out*/, int M, int K, int r,
+                         int g, void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- online, asymmetric activations ------------------------------------------- */
 /*
  * The same three calls with the asymmetric form of the Section 3 quantizer for the

@@ -35,6 +35,7 @@ SIGNATURES = {
     "dirotq_rotate_quantize": (_c_int, [_c_void_p, _c_void_p] + [_c_int] * 4 + [_c_void_p] * 4),
     "dirotq_w4a4_gemm": (_c_int, [_c_void_p] * 5 + [_c_int] * 5 + [_c_void_p, _c_int, _c_void_p]),
     "dirotq_linear": (_c_int, [_c_void_p] * 4 + [_c_int] * 5 + [_c_void_p, _c_void_p, _c_size_t, _c_void_p]),
+    "dirotq_linear_shared": (_c_int, [_c_void_p, _c_void_p, _c_int] + [_c_void_p] * 4 + [_c_int] * 4 + [_c_void_p, _c_size_t, _c_void_p]),
     "dirotq_rotate_quantize_asym": (_c_int, [_c_void_p, _c_void_p] + [_c_int] * 4 + [_c_void_p] * 5),
     "dirotq_w4a4_gemm_asym": (_c_int, [_c_void_p] * 6 + [_c_int] * 5 + [_c_void_p, _c_int, _c_void_p]),
     "dirotq_linear_asym": (_c_int, [_c_void_p] * 4 + [_c_int] * 5 + [_c_void_p, _c_void_p, _c_size_t, _c_void_p]),
@@ -212,3 +213,21 @@ def linear_asym(x, Qt, blob, N, r, g, bias=None, workspace=None, out=None):
     _check(lib().dirotq_linear_asym(_ptr(x), _ptr(Qt), _ptr(blob), _ptr(bias), M, N, K, r, g, _ptr(y),
                                     _ptr(workspace), workspace.numel(), _stream()), "dirotq_linear_asym")
     return y
+
+
+def linear_shared(x, Qt, blobs, Ns, r, g, biases=None, workspace=None, outs=None):
+    """One rotation + quantization of x, then one GEMM per (blob, N).  Returns the list of outputs."""
+    M, K = x.shape
+    n = len(blobs)
+    if workspace is None:
+        workspace = _new((workspace_bytes(M, K, r, g),), torch.uint8, x)
+    if outs is None:
+        outs = [_new((M, N), torch.bfloat16, x) for N in Ns]
+    vp = ctypes.c_void_p * n
+    c_blobs = vp(*[_ptr(b) for b in blobs])
+    c_bias = vp(*[_ptr(b) for b in biases]) if biases is not None else None
+    c_ys = vp(*[_ptr(y) for y in outs])
+    c_Ns = (ctypes.c_int * n)(*Ns)
+    _check(lib().dirotq_linear_shared(_ptr(x), _ptr(Qt), n, c_blobs, c_bias, c_Ns, c_ys, M, K, r, g, _ptr(workspace),
+                                      workspace.numel(), _stream()), "dirotq_linear_shared")
+    return outs

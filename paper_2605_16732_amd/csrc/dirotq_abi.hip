@@ -160,6 +160,35 @@ int dirotq_linear(const uint16_t* x_bf16, const uint16_t* Qt_bf16, const void* b
   return launch_w4a4_gemm(xh, xl, sx, nullptr, blob, bias_bf16, M, N, K, r, g, y_bf16, 0, (hipStream_t)stream);
 }
 
+int dirotq_linear_shared(const uint16_t* x_bf16, const uint16_t* Qt_bf16, int n_out, const void* const* blobs,
+                         const uint16_t* const* biases, const int* Ns, uint16_t* const* ys, int M, int K, int r,
+                         int g, void* workspace, size_t workspace_bytes, void* stream) {
+  if (n_out < 1 || n_out > 16) return DIROTQ_ERR_SHAPE;
+  if (!blobs || !Ns || !ys) return DIROTQ_ERR_NULL;
+  for (int i = 0; i < n_out; i++) {
+    int st = check_shape(M, Ns[i], K, r, g);
+    if (st) return st;
+  }
+  if (M == 0) return DIROTQ_OK;
+  if (!x_bf16 || !Qt_bf16 || !workspace) return DIROTQ_ERR_NULL;
+  if (misaligned(x_bf16) || misaligned(Qt_bf16) || ((uintptr_t)workspace & (kAlign - 1)) != 0) return DIROTQ_ERR_ALIGN;
+  for (int i = 0; i < n_out; i++) {
+    if (!blobs[i] || !ys[i]) return DIROTQ_ERR_NULL;
+    if (misaligned(blobs[i]) || misaligned(ys[i]) || (biases && misaligned(biases[i]))) return DIROTQ_ERR_ALIGN;
+  }
+  const WorkspaceLayout L = workspace_layout(M, K, r, g);
+  if (workspace_bytes < L.bytes) return DIROTQ_ERR_WORKSPACE;
+  char* ws = (char*)workspace;
+  uint16_t* xh = (uint16_t*)(ws + L.off_xh);
+  uint8_t* xl = (uint8_t*)(ws + L.off_xl);
+  uint16_t* sx = (uint16_t*)(ws + L.off_sx);
+  int st = launch_rotate_quantize(x_bf16, Qt_bf16, M, K, r, g, xh, xl, sx, nullptr, (hipStream_t)stream);
+  for (int i = 0; i < n_out && !st; i++)
+    st = launch_w4a4_gemm(xh, xl, sx, nullptr, blobs[i], biases ? biases[i] : nullptr, M, Ns[i], K, r, g, ys[i], 0,
+                          (hipStream_t)stream);
+  return st;
+}
+
 int dirotq_rotate_quantize_asym(const uint16_t* x_bf16, const uint16_t* Qt_bf16, int M, int K, int r, int g,
                                 uint16_t* xh_bf16, uint8_t* xl_packed, uint16_t* sx_fp16, uint16_t* zx_fp16,
                                 void* stream) {

@@ -91,6 +91,16 @@ def test_argument_errors_before_any_launch():
     assert L.dirotq_rotate_quantize_asym(a, a, 0, 64, 0, 32, None, a, a, a, None) == B.OK
     assert L.dirotq_w4a4_gemm_asym(None, a, a, a, a, None, 0, 8, 64, 0, 32, a, 0, None) == B.OK
     assert L.dirotq_linear_asym(a, a, a, None, 0, 8, 64, 0, 32, a, a, 0, None) == B.OK
+    # shared-input entry point: host arrays of device pointers
+    vp2 = (ctypes.c_void_p * 2)(a, a)
+    ns2 = (ctypes.c_int * 2)(8, 16)
+    assert L.dirotq_linear_shared(a, a, 0, vp2, None, ns2, vp2, 4, 64, 0, 32, a, 1 << 20, None) == B.ERR_SHAPE   # n_out < 1
+    assert L.dirotq_linear_shared(a, a, 17, vp2, None, ns2, vp2, 4, 64, 0, 32, a, 1 << 20, None) == B.ERR_SHAPE
+    assert L.dirotq_linear_shared(a, a, 2, None, None, ns2, vp2, 4, 64, 0, 32, a, 1 << 20, None) == B.ERR_NULL
+    assert L.dirotq_linear_shared(a, a, 2, vp2, None, (ctypes.c_int * 2)(8, 0), vp2, 4, 64, 0, 32, a, 1 << 20, None) == B.ERR_SHAPE
+    assert L.dirotq_linear_shared(a, a, 2, (ctypes.c_void_p * 2)(a, None), None, ns2, vp2, 4, 64, 0, 32, a, 1 << 20, None) == B.ERR_NULL
+    assert L.dirotq_linear_shared(a, a, 2, vp2, None, ns2, vp2, 4, 64, 0, 32, a, 16, None) == B.ERR_WORKSPACE
+    assert L.dirotq_linear_shared(a, a, 2, vp2, None, ns2, vp2, 0, 64, 0, 32, a, 0, None) == B.OK
     # M == 0 is a valid no-op and launches nothing
     assert L.dirotq_rotate_quantize(a, a, 0, 64, 0, 32, None, a, a, None) == B.OK
     assert L.dirotq_w4a4_gemm(None, a, a, a, None, 0, 8, 64, 0, 32, a, 0, None) == B.OK

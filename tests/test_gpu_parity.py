@@ -318,3 +318,29 @@ def test_deterministic_and_empty():
     torch.cuda.synchronize()
     assert torch.all(big[0] == 1.0) and torch.all(big[M + 1] == 1.0)
     assert torch.equal(big[1:M + 1], y1[:M])
+
+
+def test_shared_input_layers_equal_separate_calls():
+    """dirotq_linear_shared = one rotation + quantization feeding several GEMMs: bit-identical to
+    separate dirotq_linear calls (and therefore within the oracle's tolerance like them)."""
+    shp = I.LayerShape("shared", 300, 512, 0, 64, 64, 8, 8, 5)
+    rng = np.random.default_rng(31)
+    Ns = [192, 333, 64]
+    L = I.make_layer(I.LayerShape("shared", 300, 512, max(Ns), 64, 64, 8, 8, 5))
+    Qt = B.prepare_rotation(dev(L.Q32))
+    x = dev_bf16(L.x_bits)
+    blobs, biases, refs = [], [], []
+    for N in Ns:
+        W = (rng.standard_normal((N, shp.K)) / np.sqrt(shp.K)).astype(np.float32)
+        Wh, qw, sw = O.prepare_weights(W, L.Q32, shp.r, shp.g)
+        bias = O.round_to_bf16(rng.standard_normal(N).astype(np.float32))
+        blobs.append(import_blob(Wh, qw, sw, N, shp.K, shp.r, shp.g))
+        biases.append(dev_bf16(O.bf16_bits(bias)))
+        refs.append(O.linear(I.bf16_bits_to_f32(L.x_bits), I.bf16_bits_to_f32(L.Q_bits), Wh, qw, sw, shp.r, shp.g, bias))
+    ys = B.linear_shared(x, Qt, blobs, Ns, shp.r, shp.g, biases=biases)
+    torch.cuda.synchronize()
+    for N, blob, bias, y, ref in zip(Ns, blobs, biases, ys, refs):
+        y1 = B.linear(x, Qt, blob, N, shp.r, shp.g, bias=bias)
+        torch.cuda.synchronize()
+        assert torch.equal(y, y1)
+        check_output(O.from_bf16_bits(host_bf16_bits(y)), ref["y32"], tol=1e-2)
