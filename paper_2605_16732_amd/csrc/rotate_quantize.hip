@@ -20,6 +20,8 @@
 // refilled with stage kt+2; every store/load pair sits between MFMAs.  (On gfx950 this
 // beats the direct global_load_lds path: those instructions hold up the matrix pipe of the
 // issuing SIMD far longer than a register load plus an LDS store.)
+#include <atomic>
+
 #include "dirotq_internal.h"
 
 namespace dirotq {
@@ -506,12 +508,13 @@ static int launch_one(const uint16_t* x, const uint16_t* Qt, int M, int K, int r
   const int n_tt = (M + C::TT - 1) / C::TT;
   const long n_blocks = (long)n_ct * n_tt;
   const int per_xcd = (int)((n_blocks + 7) / 8);
-  static bool attr_done = false;
-  if (!attr_done) {
+  // (idempotent: two threads racing here would both set the same attribute)
+  static std::atomic<bool> attr_done{false};
+  if (!attr_done.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute((const void*)rotate_quantize_kernel<WGC, WGT, BK, MI, ASYM>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
     if (e != hipSuccess) return hip_failed(e);
-    attr_done = true;
+    attr_done.store(true, std::memory_order_release);
   }
   hipLaunchKernelGGL((rotate_quantize_kernel<WGC, WGT, BK, MI, ASYM>), dim3(per_xcd * 8), dim3(C::NT), C::SMEM, s, x,
                      Qt, M, K, r, g, xh, xl, sx, zx, r_pad, Kv, n_ct, n_tt, per_xcd, sx_ld);

@@ -34,6 +34,8 @@
 // unpacking, against 64 cycles of fp8 MFMA per tile and 64-channel group), so the main loop
 // is software-pipelined by hand: the MFMAs of tile s+1 are issued before the fma sweep of
 // tile s, and the LDS operand reads of the next group are issued one sweep ahead.
+#include <atomic>
+
 #include "dirotq_internal.h"
 
 namespace dirotq {
@@ -518,12 +520,13 @@ static int launch_one(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx,
   const int n_mt = (M + TM - 1) / TM, n_nt = (N + TN - 1) / TN;
   const long n_blocks = (long)n_mt * n_nt;
   const int per_xcd = (int)((n_blocks + 7) / 8);
-  static bool attr_done = false;
-  if (!attr_done) {
+  // (idempotent: two threads racing here would both set the same attribute)
+  static std::atomic<bool> attr_done{false};
+  if (!attr_done.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute((const void*)w4a4_gemm_kernel<GS, OUT_F32, ASYM>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes(GS));
     if (e != hipSuccess) return hip_failed(e);
-    attr_done = true;
+    attr_done.store(true, std::memory_order_release);
   }
   hipLaunchKernelGGL((w4a4_gemm_kernel<GS, OUT_F32, ASYM>), dim3(per_xcd * 8), dim3(NTHREADS), smem_bytes(GS), s, xh,
                      xl, sx, zx, (const uint16_t*)(bp + L.off_wh), (const uint8_t*)(bp + L.off_codes),
