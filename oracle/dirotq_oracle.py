@@ -30,6 +30,10 @@ Readings where the paper is silent (each is listed in the design notes too):
   * scales are stored as IEEE fp16 and codes are computed against the *stored*
     scale, with the fixed fp32 operation sequence of `quantize_groups`;
   * the quantizer reads the fp32 rotated activation, not a BF16-rounded copy;
+  * the W4A8 variant (`*_a8`) follows the paper's implementation details for 8-bit
+    settings on the activation side: per-token dynamic quantization, here symmetric INT8
+    over the K - r rotated channels that are not kept in BF16, one fp16 scale per token;
+    weights stay 4-bit per group;
   * the asymmetric activation variant (`*_asym`, the form the paper's experiments use
     for activations: z = min X, s = (max X - min X) / 15, codes in [0, 15]) stores the
     zero-point as fp16 next to the fp16 scale and quantizes against the stored pair.
@@ -49,6 +53,7 @@ import numpy as np
 
 QMAX = 7                       # 2^(4-1) - 1, quantizer equation, symmetric case
 UQMAX = 15                     # 2^4 - 1, quantizer equation, asymmetric case (q_min = 0)
+QMAX8 = 127                    # 2^(8-1) - 1, quantizer equation, symmetric case, 8 bits
 FP16_MAX = np.float32(65504.0)
 
 
@@ -322,6 +327,70 @@ def linear_asym(x, Q, Wh, qw, sw, r, g, bias=None):
     xh, qx, sx, zx = split_quantize_asym(xhat, r, g)
     y32, y = combine_asym(xh, qx, sx, zx, Wh, qw, sw, g, bias)
     return dict(xhat=xhat, xh=xh, qx=qx, sx=sx, zx=zx, y32=y32, y=y)
+
+
+# --------------------------------------------------------------------------
+# W4A8: 8-bit per-token activations (the paper's "per-token dynamic activation
+# quantization" for 8-bit settings), 4-bit per-group weights
+# --------------------------------------------------------------------------
+def quantize_tokens_int8(v: np.ndarray):
+    """Symmetric INT8 quantization of each row (token) with one scale.
+
+    v: float32 [M, C].  Returns (codes int8 [M, C] in [-127,127], scales float16 [M]).
+    Same fixed fp32 sequence as `quantize_groups` with q_max = 127:  amax = max|v|;
+    s32 = amax / 127;  s16 = fp16(min(s32, 65504));  sf = float32(s16);  sf == 0 -> codes 0;
+    inv = 1 / sf;  code = clip(rint(v * inv), -127, 127).
+    """
+    v = np.ascontiguousarray(v, dtype=np.float32)
+    if v.shape[1] == 0:
+        return np.zeros(v.shape, np.int8), np.zeros((v.shape[0],), np.float16)
+    amax = np.max(np.abs(v), axis=1)
+    s32 = np.minimum((amax / np.float32(QMAX8)).astype(np.float32), FP16_MAX)
+    s16 = s32.astype(np.float16)
+    sf = s16.astype(np.float32)
+    with np.errstate(divide="ignore"):
+        inv = (np.float32(1.0) / sf).astype(np.float32)
+    inv = np.where(sf == 0, np.float32(0.0), inv).astype(np.float32)
+    t = (v * inv[:, None]).astype(np.float32)
+    q = np.clip(np.rint(t), -QMAX8, QMAX8).astype(np.int8)
+    return q, s16
+
+
+def split_quantize_a8(xhat: np.ndarray, r: int):
+    """Returns (xh float32 bf16-valued [M,r], qx int8 [M,K-r], sx float16 [M])."""
+    xh = round_to_bf16(xhat[:, :r])
+    qx, sx = quantize_tokens_int8(xhat[:, r:])
+    return xh, qx, sx
+
+
+def combine_a8(xh, qx, sx, Wh, qw, sw, g, bias=None):
+    """y32[m,n] = sum_{k<r} xh Wh + sx[m] * sum_j sw[n,j] I[m,n,j] (+ bias), I the exact integer
+    dot of the INT8 activation codes with the INT4 weight codes of group j; float64, one
+    rounding to float32."""
+    M = xh.shape[0]
+    N = Wh.shape[0]
+    acc = np.asarray(xh, np.float64) @ np.asarray(Wh, np.float64).T if xh.shape[1] else np.zeros((M, N))
+    C = qx.shape[1]
+    G = C // g if C else 0
+    sx64 = np.asarray(sx).astype(np.float64)
+    sw64 = np.asarray(sw).astype(np.float64)
+    low = np.zeros((M, N))
+    for j in range(G):
+        a = qx[:, j * g:(j + 1) * g].astype(np.float64)
+        b = qw[:, j * g:(j + 1) * g].astype(np.float64)
+        low = low + (a @ b.T) * sw64[:, j][None, :]
+    acc = acc + sx64[:, None] * low
+    if bias is not None:
+        acc = acc + np.asarray(bias, np.float64)[None, :]
+    y32 = acc.astype(np.float32)
+    return y32, round_to_bf16(y32)
+
+
+def linear_a8(x, Q, Wh, qw, sw, r, g, bias=None):
+    xhat = rotate(x, Q)
+    xh, qx, sx = split_quantize_a8(xhat, r)
+    y32, y = combine_a8(xh, qx, sx, Wh, qw, sw, g, bias)
+    return dict(xhat=xhat, xh=xh, qx=qx, sx=sx, y32=y32, y=y)
 
 
 # --------------------------------------------------------------------------

@@ -316,3 +316,67 @@ def test_asym_is_closer_than_symmetric_on_shifted_activations():
     err_sym = np.abs(O.dequantize_groups(qs, ss, 64) - v).mean()
     err_asym = np.abs(O.dequantize_groups_asym(qa, sa, za, 64) - v).mean()
     assert err_asym < 0.5 * err_sym
+
+
+# ---------------------------------------------------------------------------
+# W4A8: 8-bit per-token activations
+# ---------------------------------------------------------------------------
+def _quant8(vals):
+    amax = max(abs(v) for v in vals)
+    sf = _f16(min(_f32(amax / 127.0), 65504.0))
+    if sf == 0.0:
+        return [0] * len(vals), 0.0
+    inv = _f32(1.0 / sf)
+    return [max(-127, min(127, round(_f32(v * inv)))) for v in vals], sf
+
+
+def _brute_layer_a8(x, Q, Q32, W, r, g, bias=None):
+    """Every activation replaced by q8 * s_token, every weight by q4 * s_group, exact sums."""
+    M, K, N = len(x), len(x[0]), len(W)
+    G = (K - r) // g
+    Wp = [[_f32(float(sum(Fraction(W[n][k]) * Fraction(Q32[k][c]) for k in range(K))))
+           for c in range(K)] for n in range(N)]
+    Wh = [[_bf16(Wp[n][c]) for c in range(r)] for n in range(N)]
+    wt = []
+    for n in range(N):
+        row = []
+        for j in range(G):
+            c, s = _quant(Wp[n][r + j * g: r + (j + 1) * g])
+            row += [Fraction(ci) * Fraction(s) for ci in c]
+        wt.append(row)
+    y = []
+    for m in range(M):
+        xhat = [_f32(float(sum(Fraction(x[m][k]) * Fraction(Q[k][c]) for k in range(K))))
+                for c in range(K)]
+        xh = [_bf16(v) for v in xhat[:r]]
+        c8, s8 = _quant8(xhat[r:]) if K > r else ([], 0.0)
+        xt = [Fraction(ci) * Fraction(s8) for ci in c8]
+        row = []
+        for n in range(N):
+            acc = sum(Fraction(xh[k]) * Fraction(Wh[n][k]) for k in range(r))
+            acc += sum(xt[k] * wt[n][k] for k in range(K - r))
+            if bias is not None:
+                acc += Fraction(bias[n])
+            row.append(_f32(float(acc)))
+        y.append(row)
+    return np.array(y, np.float32)
+
+
+@pytest.mark.parametrize("M,K,N,r,g", [(3, 16, 5, 0, 4), (3, 16, 5, 4, 4), (2, 12, 4, 4, 8), (4, 20, 3, 4, 16)])
+def test_a8_brute_force_tiny(M, K, N, r, g):
+    x, Q, Q32, W = _tiny(300 + K + r, M, K, N)
+    bias = np.linspace(-1, 1, N).astype(np.float32)
+    want = _brute_layer_a8(x.tolist(), Q.tolist(), Q32.tolist(), W.tolist(), r, g, bias.tolist())
+    Wh, qw, sw = O.prepare_weights(W, Q32, r, g)
+    got = O.linear_a8(x, Q, Wh, qw, sw, r, g, bias)
+    np.testing.assert_allclose(got["y32"], want, rtol=2.0 ** -22, atol=1e-30)
+    assert got["qx"].dtype == np.int8 and got["sx"].shape == (M,)
+
+
+def test_a8_is_closer_than_a4_on_the_same_layer():
+    x, Q, Q32, W = _tiny(77, 8, 64, 12)
+    Wh, qw, sw = O.prepare_weights(W, Q32, 8, 8)
+    ref = O.linear_exact(x, Q, W, 8)
+    e4 = np.abs(O.linear(x, Q, Wh, qw, sw, 8, 8)["y32"] - ref).mean()
+    e8 = np.abs(O.linear_a8(x, Q, Wh, qw, sw, 8, 8)["y32"] - ref).mean()
+    assert e8 < e4

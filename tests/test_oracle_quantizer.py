@@ -263,3 +263,50 @@ def test_asym_of_a_symmetric_two_point_group():
     q, s, z = O.quantize_groups_asym(np.array([[-a, a, -a, a]], np.float32), 4)
     np.testing.assert_array_equal(q[0], [0, 15, 0, 15])
     assert float(z[0, 0]) == -3.75 and float(s[0, 0]) == 0.5
+
+
+# ---------------------------------------------------------------------------
+# 8-bit per-token variant (W4A8)
+# ---------------------------------------------------------------------------
+GOLDEN_INT8 = os.path.join(os.path.dirname(__file__), "golden", "quantizer_int8_cases.txt")
+
+
+def _int8_cases():
+    out = []
+    with open(GOLDEN_INT8) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            vals, s_hex, codes = [p.strip() for p in line.split("|")]
+            out.append((np.array([float(v) for v in vals.split()], np.float32), int(s_hex, 16),
+                        np.array([int(c) for c in codes.split()], np.int8)))
+    return out
+
+
+@pytest.mark.parametrize("vals,s_bits,codes", _int8_cases())
+def test_int8_hand_worked_cases(vals, s_bits, codes):
+    assert O.QMAX8 == 2 ** (8 - 1) - 1 == 127
+    q, s = O.quantize_tokens_int8(vals[None, :])
+    assert q.dtype == np.int8 and s.dtype == np.float16 and s.shape == (1,)
+    assert int(s.view(np.uint16)[0]) == s_bits
+    np.testing.assert_array_equal(q[0], codes)
+
+
+def test_int8_against_pure_python_sequence_and_bounds():
+    rng = np.random.default_rng(21)
+    v = (rng.standard_normal((30, 200)) * rng.lognormal(0, 2, (30, 1))).astype(np.float32)
+    v[:, 7] *= 50                                            # an outlier channel
+    q, s = O.quantize_tokens_int8(v)
+    for i in range(v.shape[0]):
+        row = [float(t) for t in v[i]]
+        sf = _f16(min(_f32(max(abs(t) for t in row) / 127.0), 65504.0))
+        assert float(s[i]) == sf
+        inv = _f32(1.0 / sf)
+        assert list(q[i]) == [max(-127, min(127, round(_f32(t * inv)))) for t in row]
+    # one scale per token: error at most half a step (plus what fp16 rounding of s moves the top code)
+    deq = q.astype(np.float64) * s.astype(np.float64)[:, None]
+    amax = np.abs(v).max(1).astype(np.float64)
+    bound = s.astype(np.float64) / 2 * (1 + 2.0 ** -20) + 127 * np.abs(s.astype(np.float64) - amax / 127)
+    assert np.all(np.abs(deq - v) <= bound[:, None] + 1e-30)
+    assert np.all(np.abs(q).max(1) >= 126)
