@@ -63,6 +63,8 @@ def main() -> int:
                          "one dirotq_linear_shared call rotates and quantizes them once for both GEMMs")
     ap.add_argument("--asym", action="store_true",
                     help="asymmetric activation quantizer (zero-point min, 16 unsigned levels): the *_asym entry points")
+    ap.add_argument("--a8", action="store_true",
+                    help="8-bit per-token activations against the same 4-bit weights: the *_a8 entry points")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise copy of known size (256 MiB read + 256 MiB written), "
                          "the reference the FETCH_SIZE / WRITE_SIZE counters are scaled by")
@@ -117,7 +119,8 @@ def main() -> int:
             blob = B.prepare_weights(W, Q32, shp.r, shp.g)
             Wb = W.to(torch.bfloat16)                 # comparator: plain bf16 GEMM, same shape
             del Q32, W
-        ws = torch.empty(B.workspace_bytes(shp.M, shp.K, shp.r, shp.g), dtype=torch.uint8, device=dev)
+        ws_bytes = B.a8_workspace_bytes(shp.M, shp.K, shp.r) if args.a8 else B.workspace_bytes(shp.M, shp.K, shp.r, shp.g)
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
         y = torch.empty((shp.M, shp.N), dtype=torch.bfloat16, device=dev)
         G = shp.G
         parts = (torch.empty((shp.M, shp.r), dtype=torch.bfloat16, device=dev),
@@ -125,7 +128,12 @@ def main() -> int:
                  torch.empty((G, shp.M), dtype=torch.float16, device=dev))
         if args.asym:
             parts = parts + (torch.empty((G, shp.M), dtype=torch.float16, device=dev),)
-        layers.append(dict(shape=shp, x=x, Qt=Qt, blob=blob, ws=ws, y=y, Wb=Wb, parts=parts, host=L))
+        scratch = None
+        if args.a8:
+            parts = (parts[0], torch.empty((shp.M, shp.K - shp.r), dtype=torch.uint8, device=dev),
+                     torch.empty((shp.M,), dtype=torch.float16, device=dev))
+            scratch = torch.empty(B.a8_scratch_bytes(shp.M, shp.K, shp.r), dtype=torch.uint8, device=dev)
+        layers.append(dict(shape=shp, x=x, Qt=Qt, blob=blob, ws=ws, y=y, Wb=Wb, parts=parts, host=L, scratch=scratch))
         torch.cuda.synchronize()
         log(f"inputs for {shp.name} ready ({time.time() - t0:.0f} s)")
 
@@ -141,7 +149,13 @@ def main() -> int:
     f_rq = B.rotate_quantize_asym if args.asym else B.rotate_quantize
     f_gemm = B.w4a4_gemm_asym if args.asym else B.w4a4_gemm
 
-    if args.shared_input and (args.workload != "flux" or args.asym):
+    if args.a8:
+        if args.asym:
+            print("bench.py: --a8 and --asym are different activation quantizers", file=sys.stderr)
+            return 2
+        f_linear, f_gemm = B.linear_a8, B.w4a8_gemm
+
+    if args.shared_input and (args.workload != "flux" or args.asym or args.a8):
         print("bench.py: --shared-input applies to the symmetric flux workload", file=sys.stderr)
         return 2
 
@@ -194,7 +208,10 @@ def main() -> int:
         s = Ld["shape"]
         alg = algorithmic(s)
         parts = Ld["parts"]
-        tA = time_calls(lambda: f_rq(Ld["x"], Ld["Qt"], s.r, s.g, out=parts), reps)
+        if args.a8:
+            tA = time_calls(lambda: B.rotate_quantize_a8(Ld["x"], Ld["Qt"], s.r, out=parts, scratch=Ld["scratch"]), reps)
+        else:
+            tA = time_calls(lambda: f_rq(Ld["x"], Ld["Qt"], s.r, s.g, out=parts), reps)
         tB = time_calls(lambda: f_gemm(*parts, Ld["blob"], s.M, s.N, s.K, s.r, s.g, out=Ld["y"]), reps)
         tL = time_calls(lambda: f_linear(Ld["x"], Ld["Qt"], Ld["blob"], s.N, s.r, s.g, workspace=Ld["ws"],
                                          out=Ld["y"]), reps)
@@ -232,7 +249,7 @@ def main() -> int:
                     "algorithmic_flops_per_launch": flops / n_launch, "traffic": None}
     else:
         ops = sum(p["_alg"]["B_code_ops"] for p in per_layer)
-        roofline = {"kernel": "w4a4_gemm_kernel", "bound": "mfma", "dtype": "fp8",
+        roofline = {"kernel": "w4a8_gemm_kernel" if args.a8 else "w4a4_gemm_kernel", "bound": "mfma", "dtype": "fp8",
                     "achieved": ops / (sumB * 1e-3) / 1e12, "peak": PEAK_FP8_TOPS, "unit": "TOP/s",
                     "avg_launch_ms": sumB / n_launch, "launches_per_step": n_launch,
                     "algorithmic_flops_per_launch": ops / n_launch, "traffic": None}
@@ -267,7 +284,7 @@ def main() -> int:
         xs = I.bf16_bits_to_f32(L.x_bits[:Ms])
         Qb = I.bf16_bits_to_f32(L.Q_bits)
         tc = time.perf_counter()
-        O.linear(xs, Qb, Wh, qw, sw, s.r, s.g)
+        (O.linear_a8 if args.a8 else O.linear_asym if args.asym else O.linear)(xs, Qb, Wh, qw, sw, s.r, s.g)
         dt = time.perf_counter() - tc
         try:
             cores = len(os.sched_getaffinity(0))
@@ -294,7 +311,7 @@ def main() -> int:
                                 "sweep": "configs[3]: token sweep on the PixArt fc1 shape, M in {1024..32768}",
                                 "ablation": "configs[4]: rank/group grid on the FLUX fc2 shape"}[args.workload],
                    "seed": 0, "effective_ops_per_step": total_ops, "residual_rotation": args.residual_rotation,
-                   "activation_quantizer": "asymmetric" if args.asym else "symmetric",
+                   "activation_quantizer": "int8 per token" if args.a8 else "asymmetric" if args.asym else "symmetric",
                    "shared_input": bool(args.shared_input)},
         "speedup_vs_bf16_gemm": round(bf16_ms / ms_per_step, 4),
         "bf16_gemm_ms_per_step": round(bf16_ms, 4),

@@ -189,6 +189,44 @@ int dirotq_linear_asym(const uint16_t* x_bf16, const uint16_t* Qt_bf16, const vo
                        const uint16_t* bias_bf16, int M, int N, int K, int r, int g,
                        uint16_t* y_bf16 /*out*/, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- online, 8-bit per-token activations (W4A8) --------------------------------- */
+/*
+ * The paper's 8-bit activation setting (implementation details of Section 5: per-token
+ * dynamic activation quantization) on top of the same 4-bit per-group weights: channels
+ * [r, K) of x Q get one symmetric INT8 scale per token,
+ *   s32 = max|v| / 127, s16 = fp16_rne(min(s32, 65504)), inv = 1 / float(s16) (0 when
+ *   s16 == 0), code = clip(rint(v * inv), -127, 127), all IEEE fp32,
+ * and   y[m,n] = sum_{k<r} xh[m,k] Wh[n,k]
+ *              + float(sx[m]) * sum_j float(sw[n,j]) * I[m,n,j]  (+ bias[n]),
+ * I the exact integer dot product of the INT8 and INT4 codes of weight group j
+ * (per-channel weight scales are the case of equal group scales, via
+ * dirotq_import_weights).
+ *   x8[M,K-r]   one sign-magnitude byte per channel (bit 7 sign, bits 0-6 magnitude; zero is
+ *               0x00).  Within each block of 32 channels the 16 even channels come first,
+ *               then the 16 odd ones: channel c of the block sits at byte (c & 1) * 16 + c / 2.
+ *   sx_fp16[M]  one scale per token
+ * scratch: dirotq_a8_scratch_bytes bytes of device memory, 256-byte aligned (the fp32
+ * rotated channels before the token's maximum is known); contents undefined afterwards.
+ * Shape rules as above (g only constrains K - r here).  Pointer and error rules as above.
+ */
+int dirotq_a8_scratch_bytes(int M, int K, int r, size_t* bytes /*host out*/);
+
+int dirotq_rotate_quantize_a8(const uint16_t* x_bf16, const uint16_t* Qt_bf16, int M, int K, int r,
+                              uint16_t* xh_bf16 /*out*/, uint8_t* x8 /*out*/, uint16_t* sx_fp16 /*out*/,
+                              void* scratch, size_t scratch_bytes, void* stream);
+
+int dirotq_w4a8_gemm(const uint16_t* xh_bf16, const uint8_t* x8, const uint16_t* sx_fp16, const void* blob,
+                     const uint16_t* bias_bf16, int M, int N, int K, int r, int g, void* y /*out*/,
+                     int y_dtype, void* stream);
+
+/* Bytes of workspace dirotq_linear_a8 needs (x_h, x8, s_x and the scratch above). */
+int dirotq_a8_workspace_bytes(int M, int K, int r, size_t* bytes /*host out*/);
+
+/* The fused 8-bit layer: dirotq_rotate_quantize_a8 into `workspace`, then dirotq_w4a8_gemm. */
+int dirotq_linear_a8(const uint16_t* x_bf16, const uint16_t* Qt_bf16, const void* blob,
+                     const uint16_t* bias_bf16, int M, int N, int K, int r, int g,
+                     uint16_t* y_bf16 /*out*/, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -39,6 +39,11 @@ SIGNATURES = {
     "dirotq_rotate_quantize_asym": (_c_int, [_c_void_p, _c_void_p] + [_c_int] * 4 + [_c_void_p] * 5),
     "dirotq_w4a4_gemm_asym": (_c_int, [_c_void_p] * 6 + [_c_int] * 5 + [_c_void_p, _c_int, _c_void_p]),
     "dirotq_linear_asym": (_c_int, [_c_void_p] * 4 + [_c_int] * 5 + [_c_void_p, _c_void_p, _c_size_t, _c_void_p]),
+    "dirotq_a8_scratch_bytes": (_c_int, [_c_int] * 3 + [_size_p]),
+    "dirotq_a8_workspace_bytes": (_c_int, [_c_int] * 3 + [_size_p]),
+    "dirotq_rotate_quantize_a8": (_c_int, [_c_void_p, _c_void_p] + [_c_int] * 3 + [_c_void_p] * 4 + [_c_size_t, _c_void_p]),
+    "dirotq_w4a8_gemm": (_c_int, [_c_void_p] * 5 + [_c_int] * 5 + [_c_void_p, _c_int, _c_void_p]),
+    "dirotq_linear_a8": (_c_int, [_c_void_p] * 4 + [_c_int] * 5 + [_c_void_p, _c_void_p, _c_size_t, _c_void_p]),
 }
 
 
@@ -101,6 +106,14 @@ def prepare_scratch_bytes(N, K) -> int:
 
 def workspace_bytes(M, K, r, g) -> int:
     return _size("dirotq_workspace_bytes", M, K, r, g)
+
+
+def a8_scratch_bytes(M, K, r) -> int:
+    return _size("dirotq_a8_scratch_bytes", M, K, r)
+
+
+def a8_workspace_bytes(M, K, r) -> int:
+    return _size("dirotq_a8_workspace_bytes", M, K, r)
 
 
 def _new(shape, dtype, like):
@@ -231,3 +244,40 @@ def linear_shared(x, Qt, blobs, Ns, r, g, biases=None, workspace=None, outs=None
     _check(lib().dirotq_linear_shared(_ptr(x), _ptr(Qt), n, c_blobs, c_bias, c_Ns, c_ys, M, K, r, g, _ptr(workspace),
                                       workspace.numel(), _stream()), "dirotq_linear_shared")
     return outs
+
+
+def rotate_quantize_a8(x, Qt, r, out=None, scratch=None):
+    """x bf16 [M,K], Qt bf16 [K,K] -> (xh bf16 [M,r], x8 uint8 [M,K-r] sign-magnitude bytes in the
+    even|odd order of each 32-channel block, sx fp16 [M])."""
+    M, K = x.shape
+    if out is None:
+        out = (_new((M, r), torch.bfloat16, x), _new((M, K - r), torch.uint8, x), _new((M,), torch.float16, x))
+    xh, x8, sx = out
+    if scratch is None:
+        scratch = _new((a8_scratch_bytes(M, K, r),), torch.uint8, x)
+    low = r < K
+    _check(lib().dirotq_rotate_quantize_a8(_ptr(x), _ptr(Qt), M, K, r, _ptr(xh) if r else None,
+                                           _ptr(x8) if low else None, _ptr(sx) if low else None,
+                                           _ptr(scratch) if low else None, scratch.numel(), _stream()),
+           "dirotq_rotate_quantize_a8")
+    return xh, x8, sx
+
+
+def w4a8_gemm(xh, x8, sx, blob, M, N, K, r, g, bias=None, out_dtype=torch.bfloat16, out=None):
+    y = out if out is not None else torch.empty((M, N), dtype=out_dtype, device=blob.device)
+    code = {torch.bfloat16: 0, torch.float32: 1}[y.dtype]
+    low = r < K
+    _check(lib().dirotq_w4a8_gemm(_ptr(xh) if r else None, _ptr(x8) if low else None, _ptr(sx) if low else None,
+                                  _ptr(blob), _ptr(bias), M, N, K, r, g, _ptr(y), code, _stream()),
+           "dirotq_w4a8_gemm")
+    return y
+
+
+def linear_a8(x, Qt, blob, N, r, g, bias=None, workspace=None, out=None):
+    M, K = x.shape
+    if workspace is None:
+        workspace = _new((a8_workspace_bytes(M, K, r),), torch.uint8, x)
+    y = out if out is not None else _new((M, N), torch.bfloat16, x)
+    _check(lib().dirotq_linear_a8(_ptr(x), _ptr(Qt), _ptr(blob), _ptr(bias), M, N, K, r, g, _ptr(y),
+                                  _ptr(workspace), workspace.numel(), _stream()), "dirotq_linear_a8")
+    return y

@@ -118,8 +118,9 @@ int dirotq_rotate_quantize(const uint16_t* x_bf16, const uint16_t* Qt_bf16, int 
   if (misaligned(x_bf16) || misaligned(Qt_bf16) || misaligned(xh_bf16) || misaligned(xl_packed) ||
       misaligned(sx_fp16))
     return DIROTQ_ERR_ALIGN;
-  return launch_rotate_quantize(x_bf16, Qt_bf16, M, K, r, g, xh_bf16, xl_packed, sx_fp16, nullptr,
-                                (hipStream_t)stream);
+  RqOut o;
+  o.xh = xh_bf16, o.xl = xl_packed, o.sx = sx_fp16;
+  return launch_rotate_quantize(x_bf16, Qt_bf16, M, K, r, g, o, (hipStream_t)stream);
 }
 
 int dirotq_w4a4_gemm(const uint16_t* xh_bf16, const uint8_t* xl_packed, const uint16_t* sx_fp16,
@@ -155,7 +156,9 @@ int dirotq_linear(const uint16_t* x_bf16, const uint16_t* Qt_bf16, const void* b
   uint16_t* xh = (uint16_t*)(ws + L.off_xh);
   uint8_t* xl = (uint8_t*)(ws + L.off_xl);
   uint16_t* sx = (uint16_t*)(ws + L.off_sx);
-  st = launch_rotate_quantize(x_bf16, Qt_bf16, M, K, r, g, xh, xl, sx, nullptr, (hipStream_t)stream);
+  RqOut o;
+  o.xh = xh, o.xl = xl, o.sx = sx;
+  st = launch_rotate_quantize(x_bf16, Qt_bf16, M, K, r, g, o, (hipStream_t)stream);
   if (st) return st;
   return launch_w4a4_gemm(xh, xl, sx, nullptr, blob, bias_bf16, M, N, K, r, g, y_bf16, 0, (hipStream_t)stream);
 }
@@ -182,7 +185,9 @@ int dirotq_linear_shared(const uint16_t* x_bf16, const uint16_t* Qt_bf16, int n_
   uint16_t* xh = (uint16_t*)(ws + L.off_xh);
   uint8_t* xl = (uint8_t*)(ws + L.off_xl);
   uint16_t* sx = (uint16_t*)(ws + L.off_sx);
-  int st = launch_rotate_quantize(x_bf16, Qt_bf16, M, K, r, g, xh, xl, sx, nullptr, (hipStream_t)stream);
+  RqOut o;
+  o.xh = xh, o.xl = xl, o.sx = sx;
+  int st = launch_rotate_quantize(x_bf16, Qt_bf16, M, K, r, g, o, (hipStream_t)stream);
   for (int i = 0; i < n_out && !st; i++)
     st = launch_w4a4_gemm(xh, xl, sx, nullptr, blobs[i], biases ? biases[i] : nullptr, M, Ns[i], K, r, g, ys[i], 0,
                           (hipStream_t)stream);
@@ -201,10 +206,10 @@ int dirotq_rotate_quantize_asym(const uint16_t* x_bf16, const uint16_t* Qt_bf16,
   if (misaligned(x_bf16) || misaligned(Qt_bf16) || misaligned(xh_bf16) || misaligned(xl_packed) ||
       misaligned(sx_fp16) || misaligned(zx_fp16))
     return DIROTQ_ERR_ALIGN;
-  if (r == K) return launch_rotate_quantize(x_bf16, Qt_bf16, M, K, r, g, xh_bf16, nullptr, nullptr, nullptr,
-                                            (hipStream_t)stream);   // no 4-bit part: nothing to quantize
-  return launch_rotate_quantize(x_bf16, Qt_bf16, M, K, r, g, xh_bf16, xl_packed, sx_fp16, zx_fp16,
-                                (hipStream_t)stream);
+  RqOut o;
+  o.xh = xh_bf16;
+  if (r < K) o.xl = xl_packed, o.sx = sx_fp16, o.zx = zx_fp16;   // (no 4-bit part: nothing to quantize)
+  return launch_rotate_quantize(x_bf16, Qt_bf16, M, K, r, g, o, (hipStream_t)stream);
 }
 
 int dirotq_w4a4_gemm_asym(const uint16_t* xh_bf16, const uint8_t* xl_packed, const uint16_t* sx_fp16,
@@ -241,9 +246,94 @@ int dirotq_linear_asym(const uint16_t* x_bf16, const uint16_t* Qt_bf16, const vo
   uint8_t* xl = (uint8_t*)(ws + L.off_xl);
   uint16_t* sx = (uint16_t*)(ws + L.off_sx);
   uint16_t* zx = r < K ? (uint16_t*)(ws + L.off_zx) : nullptr;
-  st = launch_rotate_quantize(x_bf16, Qt_bf16, M, K, r, g, xh, xl, sx, zx, (hipStream_t)stream);
+  RqOut o;
+  o.xh = xh, o.xl = xl, o.sx = sx, o.zx = zx;
+  st = launch_rotate_quantize(x_bf16, Qt_bf16, M, K, r, g, o, (hipStream_t)stream);
   if (st) return st;
   return launch_w4a4_gemm(xh, xl, sx, zx, blob, bias_bf16, M, N, K, r, g, y_bf16, 0, (hipStream_t)stream);
+}
+
+int dirotq_a8_scratch_bytes(int M, int K, int r, size_t* bytes) {
+  if (!bytes) return DIROTQ_ERR_NULL;
+  int st = check_shape(M, 1, K, r, 32);
+  if (st) return st;
+  const WorkspaceA8Layout L = workspace_a8_layout(M, K, r);
+  *bytes = L.bytes - L.off_xf;
+  return DIROTQ_OK;
+}
+
+int dirotq_a8_workspace_bytes(int M, int K, int r, size_t* bytes) {
+  if (!bytes) return DIROTQ_ERR_NULL;
+  int st = check_shape(M, 1, K, r, 32);
+  if (st) return st;
+  *bytes = workspace_a8_layout(M, K, r).bytes;
+  return DIROTQ_OK;
+}
+
+// rotation with fp32 output into the scratch, then the per-token quantizer
+static int rotate_quantize_a8(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, uint16_t* xh, uint8_t* x8,
+                              uint16_t* sx, char* scratch, hipStream_t s) {
+  const WorkspaceA8Layout L = workspace_a8_layout(M, K, r);
+  RqOut o;
+  o.xh = xh;
+  if (r < K) o.xf = (float*)scratch, o.pmax = (float*)(scratch + (L.off_pmax - L.off_xf));
+  int st = launch_rotate_quantize(x, Qt, M, K, r, 32, o, s);
+  if (st || r == K) return st;
+  return launch_quantize_tokens(o.xf, o.pmax, M, K - r, x8, sx, s);
+}
+
+int dirotq_rotate_quantize_a8(const uint16_t* x_bf16, const uint16_t* Qt_bf16, int M, int K, int r,
+                              uint16_t* xh_bf16, uint8_t* x8, uint16_t* sx_fp16, void* scratch,
+                              size_t scratch_bytes, void* stream) {
+  int st = check_shape(M, 1, K, r, 32);
+  if (st) return st;
+  if (M == 0) return DIROTQ_OK;
+  if (!x_bf16 || !Qt_bf16) return DIROTQ_ERR_NULL;
+  if (r > 0 && !xh_bf16) return DIROTQ_ERR_NULL;
+  if (r < K && (!x8 || !sx_fp16 || !scratch)) return DIROTQ_ERR_NULL;
+  if (misaligned(x_bf16) || misaligned(Qt_bf16) || misaligned(xh_bf16) || misaligned(x8) || misaligned(sx_fp16) ||
+      ((uintptr_t)scratch & (kAlign - 1)) != 0)
+    return DIROTQ_ERR_ALIGN;
+  const WorkspaceA8Layout L = workspace_a8_layout(M, K, r);
+  if (r < K && scratch_bytes < L.bytes - L.off_xf) return DIROTQ_ERR_WORKSPACE;
+  return rotate_quantize_a8(x_bf16, Qt_bf16, M, K, r, xh_bf16, x8, sx_fp16, (char*)scratch, (hipStream_t)stream);
+}
+
+int dirotq_w4a8_gemm(const uint16_t* xh_bf16, const uint8_t* x8, const uint16_t* sx_fp16, const void* blob,
+                     const uint16_t* bias_bf16, int M, int N, int K, int r, int g, void* y, int y_dtype,
+                     void* stream) {
+  int st = check_shape(M, N, K, r, g);
+  if (st) return st;
+  if (y_dtype != 0 && y_dtype != 1) return DIROTQ_ERR_UNSUPPORTED;
+  if (M == 0) return DIROTQ_OK;
+  if (!blob || !y) return DIROTQ_ERR_NULL;
+  if (r > 0 && !xh_bf16) return DIROTQ_ERR_NULL;
+  if (r < K && (!x8 || !sx_fp16)) return DIROTQ_ERR_NULL;
+  if (misaligned(xh_bf16) || misaligned(x8) || misaligned(sx_fp16) || misaligned(blob) || misaligned(bias_bf16) ||
+      misaligned(y))
+    return DIROTQ_ERR_ALIGN;
+  return launch_w4a8_gemm(xh_bf16, x8, sx_fp16, blob, bias_bf16, M, N, K, r, g, y, y_dtype, (hipStream_t)stream);
+}
+
+int dirotq_linear_a8(const uint16_t* x_bf16, const uint16_t* Qt_bf16, const void* blob, const uint16_t* bias_bf16,
+                     int M, int N, int K, int r, int g, uint16_t* y_bf16, void* workspace, size_t workspace_bytes,
+                     void* stream) {
+  int st = check_shape(M, N, K, r, g);
+  if (st) return st;
+  if (M == 0) return DIROTQ_OK;
+  if (!x_bf16 || !Qt_bf16 || !blob || !y_bf16 || !workspace) return DIROTQ_ERR_NULL;
+  if (misaligned(x_bf16) || misaligned(Qt_bf16) || misaligned(blob) || misaligned(bias_bf16) ||
+      misaligned(y_bf16) || ((uintptr_t)workspace & (kAlign - 1)) != 0)
+    return DIROTQ_ERR_ALIGN;
+  const WorkspaceA8Layout L = workspace_a8_layout(M, K, r);
+  if (workspace_bytes < L.bytes) return DIROTQ_ERR_WORKSPACE;
+  char* ws = (char*)workspace;
+  uint16_t* xh = (uint16_t*)(ws + L.off_xh);
+  uint8_t* x8 = (uint8_t*)(ws + L.off_x8);
+  uint16_t* sx = (uint16_t*)(ws + L.off_sx);
+  st = rotate_quantize_a8(x_bf16, Qt_bf16, M, K, r, xh, x8, sx, ws + L.off_xf, (hipStream_t)stream);
+  if (st) return st;
+  return launch_w4a8_gemm(xh, x8, sx, blob, bias_bf16, M, N, K, r, g, y_bf16, 0, (hipStream_t)stream);
 }
 
 }  // extern "C"

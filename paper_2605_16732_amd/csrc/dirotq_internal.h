@@ -57,14 +57,48 @@ inline WorkspaceLayout workspace_layout(int M, int K, int r, int g) {
   return L;
 }
 
+// Workspace of dirotq_linear_a8: xh bf16 [M][r] | x8 u8 [M][K-r] | sx fp16 [M] | xf fp32 [M][K-r] |
+// pmax fp32 [ceil((K-r)/128)][M].
+struct WorkspaceA8Layout {
+  size_t off_xh, off_x8, off_sx, off_xf, off_pmax, bytes;
+};
+inline WorkspaceA8Layout workspace_a8_layout(int M, int K, int r) {
+  WorkspaceA8Layout L;
+  const size_t KL = (size_t)(K - r);
+  L.off_xh = 0;
+  L.off_x8 = align_up((size_t)M * r * 2);
+  L.off_sx = L.off_x8 + align_up((size_t)M * KL);
+  L.off_xf = L.off_sx + align_up((size_t)M * 2);
+  L.off_pmax = L.off_xf + align_up((size_t)M * KL * 4);
+  L.bytes = L.off_pmax + align_up((KL + 127) / 128 * (size_t)M * 4);
+  if (L.bytes == 0) L.bytes = kAlign;
+  return L;
+}
+
 int check_shape(long M, long N, long K, long r, long g);   // DIROTQ_OK or DIROTQ_ERR_SHAPE
 inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
 int hip_failed(hipError_t e);                               // records e, returns DIROTQ_ERR_HIP
 
 // kernel launchers (arguments already validated)
-// zx == nullptr selects the symmetric activation quantizer, otherwise the asymmetric one
-int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g,
-                           uint16_t* xh, uint8_t* xl, uint16_t* sx, uint16_t* zx, hipStream_t s);
+// Outputs of the rotation kernel.  xf != nullptr: channels [r, K) are written unquantized (fp32, with
+// the per-wave-tile absolute maxima in pmax); else zx != nullptr selects the asymmetric 4-bit
+// quantizer, zx == nullptr the symmetric one.
+struct RqOut {
+  uint16_t* xh = nullptr;
+  uint8_t* xl = nullptr;
+  uint16_t* sx = nullptr;
+  uint16_t* zx = nullptr;
+  float* xf = nullptr;
+  float* pmax = nullptr;
+};
+int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g, const RqOut& out,
+                           hipStream_t s);
+// per-token INT8 quantization of xf [M][KL] given pmax [ceil(KL/128)][M] -> x8 [M][KL], sx [M]
+int launch_quantize_tokens(const float* xf, const float* pmax, int M, int KL, uint8_t* x8, uint16_t* sx,
+                           hipStream_t s);
+int launch_w4a8_gemm(const uint16_t* xh, const uint8_t* x8, const uint16_t* sx, const void* blob,
+                     const uint16_t* bias, int M, int N, int K, int r, int g, void* y, int y_dtype,
+                     hipStream_t s);
 int launch_w4a4_gemm(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const uint16_t* zx,
                      const void* blob, const uint16_t* bias, int M, int N, int K, int r, int g, void* y,
                      int y_dtype, hipStream_t s);

@@ -52,14 +52,18 @@ struct RQ {
   __device__ static __forceinline__ int swz(int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
 };
 
-// ASYM: asymmetric activation quantizer (zero-point min, 16 unsigned levels) instead of the
-// symmetric one; zx receives the zero-points, laid out like sx.
-template <int WGC, int WGT, int BK, int MI, bool ASYM>
+// QM selects what happens to the channels [r, K): 0 = symmetric 4-bit per-group quantizer,
+// 1 = asymmetric one (zero-point min, 16 unsigned levels; zx receives the zero-points, laid out
+// like sx), 2 = no quantizer here: the fp32 values go to xf [M][K-r] and the absolute maximum of
+// every 128-channel wave tile to pmax [ceil((K-r)/128)][M] (per-token 8-bit quantization needs the
+// maximum over all channels of a token, which no single workgroup sees).
+template <int WGC, int WGT, int BK, int MI, int QM>
 __global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK>::WAVES_PER_SIMD)) void rotate_quantize_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ Qt, int M, int K, int r, int g,
     uint16_t* __restrict__ xh, uint8_t* __restrict__ xl, uint16_t* __restrict__ sx, uint16_t* __restrict__ zx,
-    int r_pad, int Kv, int n_ct, int n_tt, int per_xcd, int sx_ld) {
+    float* __restrict__ xf, float* __restrict__ pmax, int r_pad, int Kv, int n_ct, int n_tt, int per_xcd, int sx_ld) {
   using C = RQ<WGC, WGT, BK>;
+  constexpr bool ASYM = QM == 1;
   extern __shared__ __align__(16) unsigned char smem[];
 
   // consecutive workgroup ids go to different XCDs; give each XCD a contiguous run of tiles
@@ -205,6 +209,31 @@ __global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK>::WAVES_PER_SIMD)) 
     }
     const int cl0 = vb - r_pad;                               // first 4-bit channel of this wave
     const int KL = K - r;
+    if constexpr (QM == 2) {
+      // raw fp32 values (16-byte stores) and the wave tile's absolute maximum per token
+#pragma unroll
+      for (int j = 0; j < WT; j++) {
+        const int m = m0 + wt * C::WAVE_T + j * 32 + (l & 31);
+        float a = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+          const int cl = cl0 + i * 32;
+          if (cl < KL) {
+#pragma unroll
+            for (int v = 0; v < 16; v++) a = fmaxf(a, fabsf(acc[i][j][v]));
+            if (m < M) {
+#pragma unroll
+              for (int q = 0; q < 4; q++)
+                *(float4*)(xf + (size_t)m * KL + cl + 8 * q + 4 * h) =
+                    make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+            }
+          }
+        }
+        a = fmaxf(a, __shfl_xor(a, 32));
+        if (h == 0 && m < M) pmax[(size_t)(cl0 >> 7) * sx_ld + m] = a;
+      }
+      return;
+    }
     const size_t xl_ld = (size_t)KL / 2;
     const int gi_tiles = g >> 5;                              // 32-channel MFMA tiles per group: 1, 2, 4
 #pragma unroll
@@ -362,6 +391,28 @@ __global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK>::WAVES_PER_SIMD)) 
     }
     const int cl0 = vb - r_pad;                               // first 4-bit channel of this wave
     const int KL = K - r;
+    if constexpr (QM == 2) {
+#pragma unroll
+      for (int j = 0; j < NJ; j++) {
+        const int m = m0 + wt * 64 + j * 16 + lr;
+        float a = 0.0f;
+#pragma unroll
+        for (int i = 0; i < NI; i++) {
+          const int cl = cl0 + i * 16;
+          if (cl < KL) {
+#pragma unroll
+            for (int e = 0; e < 4; e++) a = fmaxf(a, fabsf(acc[i][j][e]));
+            if (m < M)
+              *(float4*)(xf + (size_t)m * KL + cl + 4 * hq) =
+                  make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+          }
+        }
+        a = fmaxf(a, __shfl_xor(a, 16));
+        a = fmaxf(a, __shfl_xor(a, 32));
+        if (hq == 0 && m < M) pmax[(size_t)(cl0 >> 7) * sx_ld + m] = a;
+      }
+      return;
+    }
     const size_t xl_ld = (size_t)KL / 2;
     const int gu = g >> 5;                                    // 32-channel units per group: 1, 2, 4
     // The four lanes of a token are the four 16-lane rows of the wave; data moves between them with
@@ -491,9 +542,10 @@ __global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK>::WAVES_PER_SIMD)) 
   }
 }
 
-template <int WGC, int WGT, int BK, int MI, bool ASYM>
+template <int WGC, int WGT, int BK, int MI, int QM>
 static int launch_one(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g, uint16_t* xh,
-                      uint8_t* xl, uint16_t* sx, uint16_t* zx, hipStream_t s, int m_off, int sx_ld) {
+                      uint8_t* xl, uint16_t* sx, uint16_t* zx, float* xf, float* pmax, hipStream_t s, int m_off,
+                      int sx_ld) {
   // tokens [m_off, m_off + M) of the caller's arrays; sx_ld = total token count (row length of s_x)
   if (sx_ld == 0) sx_ld = M;
   x += (size_t)m_off * K;
@@ -501,6 +553,8 @@ static int launch_one(const uint16_t* x, const uint16_t* Qt, int M, int K, int r
   if (xl) xl += (size_t)m_off * ((K - r) / 2);
   if (sx) sx += m_off;
   if (zx) zx += m_off;
+  if (xf) xf += (size_t)m_off * (K - r);
+  if (pmax) pmax += m_off;
   using C = RQ<WGC, WGT, BK>;
   const int r_pad = (r + 127) / 128 * 128;
   const int Kv = r_pad + (K - r + 127) / 128 * 128;
@@ -511,26 +565,27 @@ static int launch_one(const uint16_t* x, const uint16_t* Qt, int M, int K, int r
   // (idempotent: two threads racing here would both set the same attribute)
   static std::atomic<bool> attr_done{false};
   if (!attr_done.load(std::memory_order_acquire)) {
-    hipError_t e = hipFuncSetAttribute((const void*)rotate_quantize_kernel<WGC, WGT, BK, MI, ASYM>,
+    hipError_t e = hipFuncSetAttribute((const void*)rotate_quantize_kernel<WGC, WGT, BK, MI, QM>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
     if (e != hipSuccess) return hip_failed(e);
     attr_done.store(true, std::memory_order_release);
   }
-  hipLaunchKernelGGL((rotate_quantize_kernel<WGC, WGT, BK, MI, ASYM>), dim3(per_xcd * 8), dim3(C::NT), C::SMEM, s, x,
-                     Qt, M, K, r, g, xh, xl, sx, zx, r_pad, Kv, n_ct, n_tt, per_xcd, sx_ld);
+  hipLaunchKernelGGL((rotate_quantize_kernel<WGC, WGT, BK, MI, QM>), dim3(per_xcd * 8), dim3(C::NT), C::SMEM, s, x,
+                     Qt, M, K, r, g, xh, xl, sx, zx, xf, pmax, r_pad, Kv, n_ct, n_tt, per_xcd, sx_ld);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? DIROTQ_OK : hip_failed(e);
 }
 
 template <int WGC, int WGT, int BK, int MI>
-static int launch_cfg(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g, uint16_t* xh,
-                      uint8_t* xl, uint16_t* sx, uint16_t* zx, hipStream_t s, int m_off = 0, int sx_ld = 0) {
-  return zx ? launch_one<WGC, WGT, BK, MI, true>(x, Qt, M, K, r, g, xh, xl, sx, zx, s, m_off, sx_ld)
-            : launch_one<WGC, WGT, BK, MI, false>(x, Qt, M, K, r, g, xh, xl, sx, zx, s, m_off, sx_ld);
+static int launch_cfg(const RqOut& o, const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g,
+                      hipStream_t s, int m_off = 0, int sx_ld = 0) {
+  if (o.xf) return launch_one<WGC, WGT, BK, MI, 2>(x, Qt, M, K, r, g, o.xh, o.xl, o.sx, o.zx, o.xf, o.pmax, s, m_off, sx_ld);
+  if (o.zx) return launch_one<WGC, WGT, BK, MI, 1>(x, Qt, M, K, r, g, o.xh, o.xl, o.sx, o.zx, o.xf, o.pmax, s, m_off, sx_ld);
+  return launch_one<WGC, WGT, BK, MI, 0>(x, Qt, M, K, r, g, o.xh, o.xl, o.sx, o.zx, o.xf, o.pmax, s, m_off, sx_ld);
 }
 
-int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g, uint16_t* xh,
-                           uint8_t* xl, uint16_t* sx, uint16_t* zx, hipStream_t s) {
+int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g, const RqOut& o,
+                           hipStream_t s) {
   // Large problems: 256 x 256 workgroup tiles (8 waves); medium: 256 channels x 128 tokens
   // (4 waves); small: 128 x 128 (2 waves), so that the grid still covers the chip.
   // The large tiles run long enough to be limited by power (the shader clock drops under
@@ -543,11 +598,11 @@ int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, 
   const long big_tiles = n_tc256 * ((M + 255) / 256);    // 256 channels x 256 tokens
   const long mid_tiles = n_tc256 * ((M + 127) / 128);    // 256 channels x 128 tokens
 #ifdef DIROTQ_RQ_FORCE   // build-time tuning aid: -DDIROTQ_RQ_FORCE=WGC,WGT,BK,MI (K % BK must be 0)
-  return launch_cfg<DIROTQ_RQ_FORCE>(x, Qt, M, K, r, g, xh, xl, sx, zx, s);
+  return launch_cfg<DIROTQ_RQ_FORCE>(o, x, Qt, M, K, r, g, s);
 #endif
   if (K % 64 != 0) {
-    if (mid_tiles >= 100) return launch_cfg<2, 2, 32, 32>(x, Qt, M, K, r, g, xh, xl, sx, zx, s);
-    return launch_cfg<1, 2, 32, 32>(x, Qt, M, K, r, g, xh, xl, sx, zx, s);
+    if (mid_tiles >= 100) return launch_cfg<2, 2, 32, 32>(o, x, Qt, M, K, r, g, s);
+    return launch_cfg<1, 2, 32, 32>(o, x, Qt, M, K, r, g, s);
   }
   if (big_tiles >= 200) {
     // 256 CUs take one big tile each per round.  When the last round would be less than 40-60%
@@ -557,14 +612,14 @@ int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, 
     const int tt_big = (int)(full / n_tc256);               // token tiles covered by full rounds
     const long tail_max = K >= 2048 ? 150 : 104;            // short tiles pay more for the second launch
     if (full > 0 && tail > 0 && tail <= tail_max && tt_big * 256 < M && (M - tt_big * 256) % 128 == 0) {
-      int st = launch_cfg<2, 4, 64, 16>(x, Qt, tt_big * 256, K, r, g, xh, xl, sx, zx, s, 0, M);
+      int st = launch_cfg<2, 4, 64, 16>(o, x, Qt, tt_big * 256, K, r, g, s, 0, M);
       if (st) return st;
-      return launch_cfg<2, 2, 64, 32>(x, Qt, M - tt_big * 256, K, r, g, xh, xl, sx, zx, s, tt_big * 256, M);
+      return launch_cfg<2, 2, 64, 32>(o, x, Qt, M - tt_big * 256, K, r, g, s, tt_big * 256, M);
     }
-    return launch_cfg<2, 4, 64, 16>(x, Qt, M, K, r, g, xh, xl, sx, zx, s);
+    return launch_cfg<2, 4, 64, 16>(o, x, Qt, M, K, r, g, s);
   }
-  if (mid_tiles >= 100) return launch_cfg<2, 2, 64, 32>(x, Qt, M, K, r, g, xh, xl, sx, zx, s);
-  return launch_cfg<1, 2, 32, 32>(x, Qt, M, K, r, g, xh, xl, sx, zx, s);
+  if (mid_tiles >= 100) return launch_cfg<2, 2, 64, 32>(o, x, Qt, M, K, r, g, s);
+  return launch_cfg<1, 2, 32, 32>(o, x, Qt, M, K, r, g, s);
 }
 
 }  // namespace dirotq

@@ -36,14 +36,11 @@
 // tile s, and the LDS operand reads of the next group are issued one sweep ahead.
 #include <atomic>
 
-#include "dirotq_internal.h"
+#include "gemm_tail.h"
 
 namespace dirotq {
 
-constexpr int TN = 128;         // output channels per workgroup tile
-constexpr int TM = 128;         // tokens per workgroup tile
 constexpr int BKQ = 128;        // 4-bit channels per LDS stage (one 128-byte fp8 row)
-constexpr int NTHREADS = 256;   // 4 waves as 2 (n) x 2 (tokens), 64 n x 64 tokens each
 constexpr int ROWS = TN + TM;
 constexpr int STAGE_BYTES = ROWS * 128;              // fp8 [256 rows][128 B] (= bf16 [256][64])
 constexpr int SCALE_OFF = 2 * STAGE_BYTES;           // u64 [2 bufs][4 groups][256 rows]: {fp16 scale, 0, 0, 0}
@@ -51,13 +48,6 @@ constexpr int SCALE_OFF = 2 * STAGE_BYTES;           // u64 [2 bufs][4 groups][2
 constexpr int scale_buf_bytes(int gs) { return (BKQ / gs) * ROWS * 8; }
 constexpr int zero_off(int gs) { return SCALE_OFF + 2 * scale_buf_bytes(gs); }
 constexpr int smem_bytes(int gs) { return zero_off(gs) + 256; }
-
-// [rows][128 B] tiles, 16-B chunk c of row r stored at slot c ^ ((r >> 1) & 7): LDS has
-// 64 banks and serves 16-byte accesses 16 lanes per cycle, so 16 consecutive rows must
-// fall into 16 different 16-byte slots of a 256-byte bank line.
-__device__ __forceinline__ int tile_off_bytes(int row, int chunk) {
-  return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
-}
 
 // 8 sign-magnitude nibbles of a dword -> two dwords of fp8 (E4M3) bytes [s 0000 mmm], i.e. the
 // values +-m * 2^-9 (subnormals, exact): even channels, odd channels
@@ -414,101 +404,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a4_gemm_kernel(
     }
   }
 
-  // ---- 16-bit branch: acc += W'_h x_h^T, bf16 MFMA, 64 channels per pass ----------
-  if (r > 0) {
-    const int lrow = t >> 3, lchunk = t & 7;   // 8 rows (stride 32) x one 16-B chunk per thread
-    const uint16_t* src[8];
-#pragma unroll
-    for (int i = 0; i < 8; i++) {
-      const int row = lrow + 32 * i;
-      src[i] = (row < TN ? wh + (size_t)min(n0 + row, N - 1) * r : xh + (size_t)min(m0 + row - TN, M - 1) * r) +
-               lchunk * 8;
-    }
-    // the next pass is loaded into registers while the current one is multiplied; channels past r
-    // re-read the row's last chunk and are zeroed (unconditional loads, no control flow between them)
-    uint4 v[8];
-    auto fetch = [&](int k0) {
-      const int off = min(k0 + lchunk * 8, r - 8) - lchunk * 8;
-#pragma unroll
-      for (int i = 0; i < 8; i++) v[i] = *(const uint4*)(src[i] + off);
-    };
-    fetch(0);
-    for (int k0 = 0; k0 < r; k0 += 64) {
-      const bool ok = k0 + lchunk * 8 < r;
-      __syncthreads();
-#pragma unroll
-      for (int i = 0; i < 8; i++)
-        *(uint4*)(smem + tile_off_bytes(lrow + 32 * i, lchunk)) = ok ? v[i] : make_uint4(0, 0, 0, 0);
-      fetch(min(k0 + 64, r - 8));                // past the end: a harmless re-read, never used
-      __syncthreads();
-#pragma unroll
-      for (int ks = 0; ks < 4; ks++) {
-        bf16x8 a[2], b[2];
-        const int chunk = 2 * ks + h;
-#pragma unroll
-        for (int i = 0; i < 2; i++) a[i] = *(const bf16x8*)(smem + rowA[i] * 128 + ((chunk ^ swz) << 4));
-#pragma unroll
-        for (int j = 0; j < 2; j++) b[j] = *(const bf16x8*)(smem + rowB[j] * 128 + ((chunk ^ swz) << 4));
-#pragma unroll
-        for (int i = 0; i < 2; i++)
-#pragma unroll
-          for (int j = 0; j < 2; j++)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-      }
-    }
-  }
-
-  // ---- epilogue: 4 consecutive output channels per register quad ------------------
-  const bool vec_ok = (N % 4) == 0;
-#pragma unroll
-  for (int j = 0; j < 2; j++) {
-    const int m = m0 + wt * 64 + j * 32 + (l & 31);
-    if (m >= M) continue;
-#pragma unroll
-    for (int i = 0; i < 2; i++)
-#pragma unroll
-      for (int q = 0; q < 4; q++) {
-        const int n = n0 + wn * 64 + i * 32 + 8 * q + 4 * h;
-        if (n >= N) continue;
-        float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-        const bool full = vec_ok && n + 4 <= N;
-        if (bias) {
-          if (full) {
-            const uint2 bb = *(const uint2*)(bias + n);
-            v[0] += bf16_bits_to_f32((uint16_t)(bb.x & 0xFFFF));
-            v[1] += bf16_bits_to_f32((uint16_t)(bb.x >> 16));
-            v[2] += bf16_bits_to_f32((uint16_t)(bb.y & 0xFFFF));
-            v[3] += bf16_bits_to_f32((uint16_t)(bb.y >> 16));
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; e++)
-              if (n + e < N) v[e] += bf16_bits_to_f32(bias[n + e]);
-          }
-        }
-        if (OUT_F32) {
-          float* dst = (float*)y + (size_t)m * N + n;
-          if (full) {
-            *(float4*)dst = make_float4(v[0], v[1], v[2], v[3]);
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; e++)
-              if (n + e < N) dst[e] = v[e];
-          }
-        } else {
-          uint16_t* dst = (uint16_t*)y + (size_t)m * N + n;
-          if (full) {
-            uint2 o;
-            o.x = f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16);
-            o.y = f32_to_bf16_bits(v[2]) | ((uint32_t)f32_to_bf16_bits(v[3]) << 16);
-            *(uint2*)dst = o;
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; e++)
-              if (n + e < N) dst[e] = f32_to_bf16_bits(v[e]);
-          }
-        }
-      }
-  }
+  gemm_tail<OUT_F32>(acc, smem, xh, wh, bias, y, M, N, r, m0, n0, rowA, rowB);
 }
 
 template <int GS, bool OUT_F32, bool ASYM>

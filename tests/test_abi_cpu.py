@@ -45,6 +45,11 @@ def test_size_queries():
     assert B.workspace_bytes(256, K, r, g) == pad(256 * r * 2) + pad(256 * (K - r) // 2) + 2 * pad(G * 256 * 2)
     assert B.prepare_scratch_bytes(N, K) == N * K * 4
     assert B.workspace_bytes(0, K, r, g) >= 0
+    # 8-bit activations: xh | x8 u8 [M,K-r] | sx fp16 [M] | scratch = fp32 [M,K-r] | fp32 [ceil((K-r)/128),M]
+    M, KL = 256, K - r
+    scratch = pad(M * KL * 4) + pad((KL + 127) // 128 * M * 4)
+    assert B.a8_scratch_bytes(M, K, r) == scratch
+    assert B.a8_workspace_bytes(M, K, r) == pad(M * r * 2) + pad(M * KL) + pad(M * 2) + scratch
 
 
 @pytest.mark.parametrize("N,K,r,g", [
@@ -101,6 +106,23 @@ def test_argument_errors_before_any_launch():
     assert L.dirotq_linear_shared(a, a, 2, (ctypes.c_void_p * 2)(a, None), None, ns2, vp2, 4, 64, 0, 32, a, 1 << 20, None) == B.ERR_NULL
     assert L.dirotq_linear_shared(a, a, 2, vp2, None, ns2, vp2, 4, 64, 0, 32, a, 16, None) == B.ERR_WORKSPACE
     assert L.dirotq_linear_shared(a, a, 2, vp2, None, ns2, vp2, 0, 64, 0, 32, a, 0, None) == B.OK
+    # 8-bit-activation entry points
+    assert L.dirotq_a8_scratch_bytes(4, 64, 0, None) == B.ERR_NULL
+    assert L.dirotq_a8_workspace_bytes(4, 48, 0, ctypes.byref(ctypes.c_size_t())) == B.ERR_SHAPE
+    A = 0x1000                      # 256-byte aligned
+    assert L.dirotq_rotate_quantize_a8(a, a, 4, 64, 0, None, None, a, A, 1 << 20, None) == B.ERR_NULL     # x8 needed
+    assert L.dirotq_rotate_quantize_a8(a, a, 4, 64, 0, None, a, a, None, 1 << 20, None) == B.ERR_NULL     # scratch needed
+    assert L.dirotq_rotate_quantize_a8(a, a, 4, 64, 0, None, a, a, A + 16, 1 << 20, None) == B.ERR_ALIGN
+    assert L.dirotq_rotate_quantize_a8(a, a, 4, 64, 0, None, a, a, A, 16, None) == B.ERR_WORKSPACE
+    assert L.dirotq_rotate_quantize_a8(a, a, 4, 64, 16, a, a, a, A, 1 << 20, None) == B.ERR_SHAPE
+    assert L.dirotq_rotate_quantize_a8(a, a, 0, 64, 0, None, a, a, A, 0, None) == B.OK
+    assert L.dirotq_w4a8_gemm(None, a, None, a, None, 4, 8, 64, 0, 32, a, 0, None) == B.ERR_NULL           # sx needed
+    assert L.dirotq_w4a8_gemm(None, a, a, a, None, 4, 8, 64, 0, 32, a, 2, None) == B.ERR_UNSUPPORTED
+    assert L.dirotq_w4a8_gemm(None, a, a, a, None, 4, 8, 64, 0, 48, a, 0, None) == B.ERR_SHAPE
+    assert L.dirotq_w4a8_gemm(None, a, a, a, None, 0, 8, 64, 0, 32, a, 0, None) == B.OK
+    assert L.dirotq_linear_a8(a, a, a, None, 4, 8, 64, 0, 32, a, A, 16, None) == B.ERR_WORKSPACE
+    assert L.dirotq_linear_a8(a, a, a, None, 4, 8, 64, 0, 32, a, None, 1 << 20, None) == B.ERR_NULL
+    assert L.dirotq_linear_a8(a, a, a, None, 0, 8, 64, 0, 32, a, A, 0, None) == B.OK
     # M == 0 is a valid no-op and launches nothing
     assert L.dirotq_rotate_quantize(a, a, 0, 64, 0, 32, None, a, a, None) == B.OK
     assert L.dirotq_w4a4_gemm(None, a, a, a, None, 0, 8, 64, 0, 32, a, 0, None) == B.OK
