@@ -34,6 +34,10 @@ Readings where the paper is silent (each is listed in the design notes too):
     settings on the activation side: per-token dynamic quantization, here symmetric INT8
     over the K - r rotated channels that are not kept in BF16, one fp16 scale per token;
     weights stay 4-bit per group;
+  * the W4A16 layers (`linear_w4a16`: the appendix on quantization details keeps the input
+    activations of some layers in 16 bits) are read as weight-only quantization without
+    rotation: BF16 activations against the same per-group 4-bit weights, dequantized
+    exactly (code x fp16 scale);
   * the asymmetric activation variant (`*_asym`, the form the paper's experiments use
     for activations: z = min X, s = (max X - min X) / 15, codes in [0, 15]) stores the
     zero-point as fp16 next to the fp16 scale and quantizes against the stored pair.
@@ -42,7 +46,8 @@ Pins (see tests/test_oracle_*.py): hand-worked quantizer cases from the quantize
 equation, nibble packing bytes, a pure-Python-loop brute force of the whole layer on
 tiny shapes, the identity X W = X V V^T W (exact mode, any r), reduction to a plain
 BF16 GEMM at r = K, reduction to plain per-group RTN at Q = I, quantizer error
-bounds; for the asymmetric variant hand-worked cases, shift equivariance, its error
+bounds; for the W4A16 layer a Python-loop brute force, exact integer and power-of-two cases
+and agreement with `combine` on activations that are themselves code x scale; for the asymmetric variant hand-worked cases, shift equivariance, its error
 bound, and a brute force that dequantizes every element (q s + z) and multiplies
 out, which pins the zero-point term of `combine_asym`.  Unpinned: absolute QSNR / image-quality numbers of the paper (they need
 its models and data) -- "parity unpinned" for those, none of which is computed here.
@@ -391,6 +396,22 @@ def linear_a8(x, Q, Wh, qw, sw, r, g, bias=None):
     xh, qx, sx = split_quantize_a8(xhat, r)
     y32, y = combine_a8(xh, qx, sx, Wh, qw, sw, g, bias)
     return dict(xhat=xhat, xh=xh, qx=qx, sx=sx, y32=y32, y=y)
+
+
+# --------------------------------------------------------------------------
+# W4A16: layers whose input activations stay in 16 bits (appendix "Quantization
+# details"); weights quantized per group with the Section 3 quantizer, no rotation
+# --------------------------------------------------------------------------
+def linear_w4a16(x, qw, sw, g, bias=None):
+    """y32[m,n] = sum_k x[m,k] * (qw[n,k] * sw[n, k // g]) (+ bias[n]) in float64, rounded once to
+    float32; y = bf16(y32).  x: bf16-valued float32 [M,K]; qw int8 [N,K]; sw float16 [N,K/g].
+    Returns (y32, y_bf16_valued)."""
+    Wd = dequantize_groups(qw, sw, g)                       # float64, exact
+    acc = np.asarray(x, np.float64) @ Wd.T
+    if bias is not None:
+        acc = acc + np.asarray(bias, np.float64)[None, :]
+    y32 = acc.astype(np.float32)
+    return y32, round_to_bf16(y32)
 
 
 # --------------------------------------------------------------------------

@@ -380,3 +380,60 @@ def test_a8_is_closer_than_a4_on_the_same_layer():
     e4 = np.abs(O.linear(x, Q, Wh, qw, sw, 8, 8)["y32"] - ref).mean()
     e8 = np.abs(O.linear_a8(x, Q, Wh, qw, sw, 8, 8)["y32"] - ref).mean()
     assert e8 < e4
+
+
+# --------------------------------------------------------------------------
+# W4A16: 16-bit activations against the 4-bit per-group weights, no rotation
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("M,K,N,g", [(3, 16, 5, 4), (2, 24, 4, 8), (4, 16, 3, 16)])
+def test_w4a16_brute_force_tiny(M, K, N, g):
+    """Python loops, exact rational sums: every weight is code * stored scale of its group."""
+    x, _, _, W = _tiny(500 + K + g, M, K, N)
+    bias = np.linspace(-2, 1, N).astype(np.float32)
+    qw, sw = O.quantize_groups(W, g)
+    want = np.zeros((M, N), np.float32)
+    for m in range(M):
+        for n in range(N):
+            acc = Fraction(float(bias[n]))
+            for k in range(K):
+                c, s = _quant([float(v) for v in W[n, (k // g) * g:(k // g + 1) * g]])
+                acc += Fraction(float(x[m, k])) * Fraction(c[k % g]) * Fraction(s)
+            want[m, n] = _f32(float(acc))
+    y32, y = O.linear_w4a16(x, qw, sw, g, bias)
+    np.testing.assert_allclose(y32, want, rtol=2.0 ** -22, atol=1e-30)
+    np.testing.assert_array_equal(y, O.round_to_bf16(y32))
+
+
+def test_w4a16_integer_and_power_of_two_cases():
+    """Unit scales and integer activations: a plain integer matrix product; power-of-two scales
+    per group scale exactly that group's share (a wrong group index or a transposed scale fails)."""
+    rng = np.random.default_rng(5)
+    M, K, N, g = 5, 32, 6, 8
+    x = rng.integers(-20, 21, size=(M, K)).astype(np.float32)
+    qw = rng.integers(-7, 8, size=(N, K)).astype(np.int8)
+    one = np.ones((N, K // g), np.float16)
+    y32, _ = O.linear_w4a16(x, qw, one, g)
+    np.testing.assert_array_equal(y32, (x.astype(np.int64) @ qw.astype(np.int64).T).astype(np.float32))
+    sw = (2.0 ** rng.integers(-3, 4, size=(N, K // g))).astype(np.float16)
+    y32, _ = O.linear_w4a16(x, qw, sw, g)
+    want = np.zeros((M, N))
+    for n in range(N):
+        for j in range(K // g):
+            want[:, n] += float(sw[n, j]) * (x[:, j * g:(j + 1) * g].astype(np.int64) @ qw[n, j * g:(j + 1) * g].astype(np.int64))
+    np.testing.assert_array_equal(y32, want.astype(np.float32))
+
+
+def test_w4a16_agrees_with_the_w4a4_combine_on_code_times_scale_activations():
+    """If the 16-bit activations happen to be code * scale per group (exactly representable), the
+    W4A16 product equals the W4A4 combine of those codes and scales: two separately written sums."""
+    rng = np.random.default_rng(6)
+    M, K, N, g = 7, 48, 9, 16
+    qx = rng.integers(-7, 8, size=(M, K)).astype(np.int8)
+    sx = (2.0 ** rng.integers(-4, 3, size=(M, K // g))).astype(np.float16)
+    x = O.dequantize_groups(qx, sx, g).astype(np.float32)
+    assert np.array_equal(O.round_to_bf16(x), x)
+    qw = rng.integers(-7, 8, size=(N, K)).astype(np.int8)
+    sw = rng.lognormal(-3, 1, size=(N, K // g)).astype(np.float16)
+    y_a, _ = O.linear_w4a16(x, qw, sw, g)
+    y_b, _ = O.combine(np.zeros((M, 0), np.float32), qx, sx, np.zeros((N, 0), np.float32), qw, sw, g)
+    np.testing.assert_array_equal(y_a, y_b)
