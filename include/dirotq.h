@@ -227,6 +227,19 @@ int dirotq_linear_a8(const uint16_t* x_bf16, const uint16_t* Qt_bf16, const void
                      const uint16_t* bias_bf16, int M, int N, int K, int r, int g,
                      uint16_t* y_bf16 /*out*/, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- W4A16 layers ----------------------------------------------------------------- */
+/*
+ * Layers whose input activations stay in 16 bits (the paper's appendix on quantization
+ * details): weight-only quantization, no rotation,
+ *   y[m,n] = sum_j float(sw[n,j]) * sum_{k in group j} x[m,k] * q_w[n,k]  (+ bias[n]),
+ * products exact, sums in fp32.  x_bf16 [M,K] row-major.  blob: a prepared-weight blob
+ * with r = 0 (dirotq_import_weights, or dirotq_prepare_weights with Q the identity).
+ * bias_bf16 [N] may be NULL.  y_dtype 0: y is bf16 [M,N]; 1: fp32 [M,N].  No workspace.
+ * Shape, pointer and error rules as for dirotq_w4a4_gemm.
+ */
+int dirotq_w4a16_gemm(const uint16_t* x_bf16, const void* blob, const uint16_t* bias_bf16, int M, int N,
+                      int K, int g, void* y /*out*/, int y_dtype, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

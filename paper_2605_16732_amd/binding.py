@@ -44,6 +44,7 @@ SIGNATURES = {
     "dirotq_rotate_quantize_a8": (_c_int, [_c_void_p, _c_void_p] + [_c_int] * 3 + [_c_void_p] * 4 + [_c_size_t, _c_void_p]),
     "dirotq_w4a8_gemm": (_c_int, [_c_void_p] * 5 + [_c_int] * 5 + [_c_void_p, _c_int, _c_void_p]),
     "dirotq_linear_a8": (_c_int, [_c_void_p] * 4 + [_c_int] * 5 + [_c_void_p, _c_void_p, _c_size_t, _c_void_p]),
+    "dirotq_w4a16_gemm": (_c_int, [_c_void_p] * 3 + [_c_int] * 4 + [_c_void_p, _c_int, _c_void_p]),
 }
 
 
@@ -280,4 +281,14 @@ def linear_a8(x, Qt, blob, N, r, g, bias=None, workspace=None, out=None):
     y = out if out is not None else _new((M, N), torch.bfloat16, x)
     _check(lib().dirotq_linear_a8(_ptr(x), _ptr(Qt), _ptr(blob), _ptr(bias), M, N, K, r, g, _ptr(y),
                                   _ptr(workspace), workspace.numel(), _stream()), "dirotq_linear_a8")
+    return y
+
+
+def w4a16_gemm(x, blob, N, g, bias=None, out_dtype=torch.bfloat16, out=None):
+    """x bf16 [M,K] against a prepared r = 0 blob -> y [M,N]."""
+    M, K = x.shape
+    y = out if out is not None else torch.empty((M, N), dtype=out_dtype, device=x.device)
+    code = {torch.bfloat16: 0, torch.float32: 1}[y.dtype]
+    _check(lib().dirotq_w4a16_gemm(_ptr(x), _ptr(blob), _ptr(bias), M, N, K, g, _ptr(y), code, _stream()),
+           "dirotq_w4a16_gemm")
     return y

@@ -336,4 +336,15 @@ int dirotq_linear_a8(const uint16_t* x_bf16, const uint16_t* Qt_bf16, const void
   return launch_w4a8_gemm(xh, x8, sx, blob, bias_bf16, M, N, K, r, g, y_bf16, 0, (hipStream_t)stream);
 }
 
+int dirotq_w4a16_gemm(const uint16_t* x_bf16, const void* blob, const uint16_t* bias_bf16, int M, int N, int K,
+                      int g, void* y, int y_dtype, void* stream) {
+  int st = check_shape(M, N, K, 0, g);
+  if (st) return st;
+  if (y_dtype != 0 && y_dtype != 1) return DIROTQ_ERR_UNSUPPORTED;
+  if (M == 0) return DIROTQ_OK;
+  if (!x_bf16 || !blob || !y) return DIROTQ_ERR_NULL;
+  if (misaligned(x_bf16) || misaligned(blob) || misaligned(bias_bf16) || misaligned(y)) return DIROTQ_ERR_ALIGN;
+  return launch_w4a16_gemm(x_bf16, blob, bias_bf16, M, N, K, g, y, y_dtype, (hipStream_t)stream);
+}
+
 }  // extern "C"

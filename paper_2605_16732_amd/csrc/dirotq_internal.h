@@ -99,6 +99,8 @@ int launch_quantize_tokens(const float* xf, const float* pmax, int M, int KL, ui
 int launch_w4a8_gemm(const uint16_t* xh, const uint8_t* x8, const uint16_t* sx, const void* blob,
                      const uint16_t* bias, int M, int N, int K, int r, int g, void* y, int y_dtype,
                      hipStream_t s);
+int launch_w4a16_gemm(const uint16_t* x, const void* blob, const uint16_t* bias, int M, int N, int K, int g, void* y,
+                      int y_dtype, hipStream_t s);
 int launch_w4a4_gemm(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const uint16_t* zx,
                      const void* blob, const uint16_t* bias, int M, int N, int K, int r, int g, void* y,
                      int y_dtype, hipStream_t s);

@@ -123,6 +123,12 @@ def test_argument_errors_before_any_launch():
     assert L.dirotq_linear_a8(a, a, a, None, 4, 8, 64, 0, 32, a, A, 16, None) == B.ERR_WORKSPACE
     assert L.dirotq_linear_a8(a, a, a, None, 4, 8, 64, 0, 32, a, None, 1 << 20, None) == B.ERR_NULL
     assert L.dirotq_linear_a8(a, a, a, None, 0, 8, 64, 0, 32, a, A, 0, None) == B.OK
+    # W4A16
+    assert L.dirotq_w4a16_gemm(None, a, None, 4, 8, 64, 32, a, 0, None) == B.ERR_NULL
+    assert L.dirotq_w4a16_gemm(a, a, None, 4, 8, 64, 32, a, 5, None) == B.ERR_UNSUPPORTED
+    assert L.dirotq_w4a16_gemm(a, a, None, 4, 8, 96, 64, a, 0, None) == B.ERR_SHAPE
+    assert L.dirotq_w4a16_gemm(a + 4, a, None, 4, 8, 64, 32, a, 0, None) == B.ERR_ALIGN
+    assert L.dirotq_w4a16_gemm(a, a, None, 0, 8, 64, 32, a, 0, None) == B.OK
     # M == 0 is a valid no-op and launches nothing
     assert L.dirotq_rotate_quantize(a, a, 0, 64, 0, 32, None, a, a, None) == B.OK
     assert L.dirotq_w4a4_gemm(None, a, a, a, None, 0, 8, 64, 0, 32, a, 0, None) == B.OK

@@ -1,0 +1,115 @@
+"""GPU parity of the W4A16 layer (16-bit activations against 4-bit per-group weights, no rotation)
+with the oracle, through the C ABI: integer cases bit-exact, everything else differs from the
+oracle only by the order of fp32 additions."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import dirotq_oracle as O
+from paper_2605_16732_amd import binding as B
+from paper_2605_16732_amd import inputs as I
+
+from gpu_util import check_output, dev, dev_bf16, host_bf16_bits, import_blob
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(f"[gpu-test] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def _blob(qw, sw, N, K, g):
+    return import_blob(np.zeros((N, 0), np.float32), qw, sw, N, K, 0, g)
+
+
+@pytest.mark.parametrize("M,N,K,g", [(130, 200, 256, 32), (257, 136, 448, 64), (64, 129, 384, 128), (5, 8, 64, 32),
+                                     (70, 40, 96, 32), (33, 130, 32, 32), (129, 257, 1152, 64)])
+def test_w4a16_integer_exact(M, N, K, g):
+    """Unit scales, small-integer activations: an integer matrix product below 2^24, exact in fp32
+    (every code value, odd 32-channel counts, every group size, ragged tiles)."""
+    _say(f"w4a16 integer M={M} N={N} K={K} g={g}")
+    rng = np.random.default_rng(51)
+    x = rng.integers(-100, 101, size=(M, K)).astype(np.float32)
+    qw = rng.integers(-7, 8, size=(N, K)).astype(np.int8)
+    qw[0, :] = -7
+    qw[-1, :15] = np.arange(-7, 8)
+    y = B.w4a16_gemm(dev_bf16(O.bf16_bits(x)), _blob(qw, np.ones((N, K // g), np.float16), N, K, g), N, g,
+                     out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    want = (x.astype(np.int64) @ qw.astype(np.int64).T).astype(np.float32)
+    np.testing.assert_array_equal(y.cpu().numpy(), want)
+
+
+def test_w4a16_one_hot_activations_read_back_every_weight():
+    """x = identity picks out the dequantized weight matrix itself: code * scale, channel by channel."""
+    K, N, g = 256, 136, 64
+    rng = np.random.default_rng(52)
+    qw = rng.integers(-7, 8, size=(N, K)).astype(np.int8)
+    sw = (2.0 ** rng.integers(-6, 3, size=(N, K // g))).astype(np.float16)
+    y = B.w4a16_gemm(dev_bf16(O.bf16_bits(np.eye(K, dtype=np.float32))), _blob(qw, sw, N, K, g), N, g,
+                     out_dtype=torch.float32).cpu().numpy()
+    np.testing.assert_array_equal(y, O.dequantize_groups(qw, sw, g).T.astype(np.float32))
+
+
+@pytest.mark.parametrize("M,N,K,g,use_bias", [
+    (200, 136, 320, 64, True), (130, 129, 288, 32, False), (64, 64, 256, 128, True),
+    (300, 264, 1152, 64, False), (140, 72, 3072, 64, False), (77, 50, 160, 32, True),
+])
+def test_w4a16_matches_oracle(M, N, K, g, use_bias):
+    """Same inputs on both sides: only the order of the fp32 additions differs."""
+    _say(f"w4a16 vs oracle M={M} N={N} K={K} g={g} bias={use_bias}")
+    rng = np.random.default_rng(53)
+    x = O.round_to_bf16((rng.standard_normal((M, K)) * rng.lognormal(0, 1, size=(1, K))).astype(np.float32))
+    W = (rng.standard_normal((N, K)) / np.sqrt(K)).astype(np.float32)
+    qw, sw = O.quantize_groups(W, g)
+    bias = O.round_to_bf16(rng.standard_normal(N).astype(np.float32)) if use_bias else None
+    y32, ybf = O.linear_w4a16(x, qw, sw, g, bias)
+    blob = _blob(qw, sw, N, K, g)
+    bias_d = dev_bf16(O.bf16_bits(bias)) if use_bias else None
+    xd = dev_bf16(O.bf16_bits(x))
+    yf = B.w4a16_gemm(xd, blob, N, g, bias=bias_d, out_dtype=torch.float32).cpu().numpy()
+    yb = B.w4a16_gemm(xd, blob, N, g, bias=bias_d, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    scale = np.abs(y32).max()
+    assert np.abs(yf - y32).max() <= 1e-5 * scale
+    assert np.abs(O.from_bf16_bits(host_bf16_bits(yb)) - ybf).max() <= 2.0 ** -7 * scale
+    check_output(O.from_bf16_bits(host_bf16_bits(yb)), y32, tol=1e-2)
+
+
+def test_w4a16_prepared_blob_with_identity_rotation():
+    """dirotq_prepare_weights with Q = I quantizes W itself: the blob the header tells callers to use."""
+    rng = np.random.default_rng(54)
+    M, N, K, g = 150, 200, 384, 64
+    W = (rng.standard_normal((N, K)) / np.sqrt(K)).astype(np.float32)
+    x = O.round_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
+    blob = B.prepare_weights(dev(W), dev(np.eye(K, dtype=np.float32)), 0, g)
+    qw, sw = O.quantize_groups(W, g)
+    y32, _ = O.linear_w4a16(x, qw, sw, g)
+    y = B.w4a16_gemm(dev_bf16(O.bf16_bits(x)), blob, N, g, out_dtype=torch.float32).cpu().numpy()
+    assert np.abs(y - y32).max() <= 1e-5 * np.abs(y32).max()
+
+
+def test_w4a16_pixart_fc2_full_launch_sampled_rows():
+    """The PixArt-shaped down-projection (the layer the paper keeps at W4A16) at full size; the oracle
+    recomputes sampled tokens."""
+    shp = I.PIXART[3]
+    L = I.make_layer(shp)
+    x = I.bf16_bits_to_f32(L.x_bits)
+    g = shp.g
+    qw, sw = O.quantize_groups(L.W, g)
+    rows = np.sort(np.random.default_rng(55).choice(shp.M, size=32, replace=False))
+    y32, _ = O.linear_w4a16(x[rows], qw, sw, g)
+    y = B.w4a16_gemm(dev_bf16(L.x_bits), _blob(qw, sw, shp.N, shp.K, g), shp.N, g)
+    torch.cuda.synchronize()
+    row_err, max_err = check_output(O.from_bf16_bits(host_bf16_bits(y))[rows], y32, tol=1e-2)
+    _say(f"{shp.name} w4a16: out row-rel {row_err:.2e} max-rel {max_err:.2e}")
+
+
+def test_w4a16_empty():
+    qw = np.zeros((8, 64), np.int8)
+    blob = _blob(qw, np.ones((8, 2), np.float16), 8, 64, 32)
+    y = B.w4a16_gemm(torch.empty((0, 64), dtype=torch.bfloat16, device="cuda"), blob, 8, 32)
+    assert y.shape == (0, 8)
