@@ -47,6 +47,80 @@ def algorithmic(shape):
     }
 
 
+def bench_w4a16(args, shapes, B, I, np, torch) -> int:
+    """The W4A16 GEMM on every layer shape of the workload (weights quantized without rotation
+    by dirotq_prepare_weights with Q = I), against the bf16 GEMM of the same shape."""
+    dev = "cuda"
+    layers = []
+    for shp in shapes:
+        L = I.make_layer(shp)
+        W = torch.from_numpy(L.W).to(dev)
+        blob = B.prepare_weights(W, torch.eye(shp.K, dtype=torch.float32, device=dev), 0, shp.g)
+        x = torch.from_numpy(np.ascontiguousarray(L.x_bits).view(np.int16)).to(dev).view(torch.bfloat16)
+        layers.append(dict(shape=shp, x=x, blob=blob, Wb=W.to(torch.bfloat16),
+                           y=torch.empty((shp.M, shp.N), dtype=torch.bfloat16, device=dev)))
+        del W
+        torch.cuda.synchronize()
+        log(f"inputs for {shp.name} ready")
+
+    def step():
+        for Ld in layers:
+            s = Ld["shape"]
+            B.w4a16_gemm(Ld["x"], Ld["blob"], s.N, s.g, out=Ld["y"])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    total_ops = sum(2.0 * Ld["shape"].M * Ld["shape"].N * Ld["shape"].K for Ld in layers)
+    value = total_ops / (ms_per_step * 1e-3) / 1e12
+    per_layer, sum_ms, bf16_ms = [], 0.0, 0.0
+    for Ld in layers:
+        s = Ld["shape"]
+        ts, tg = [], []
+        yb = torch.empty_like(Ld["y"])
+        for fn, acc in ((lambda: B.w4a16_gemm(Ld["x"], Ld["blob"], s.N, s.g, out=Ld["y"]), ts),
+                        (lambda: torch.matmul(Ld["x"], Ld["Wb"].t(), out=yb), tg)):
+            fn()
+            torch.cuda.synchronize()
+            for _ in range(max(5, args.steps)):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                fn()
+                b.record()
+                torch.cuda.synchronize()
+                acc.append(a.elapsed_time(b))
+        t, g_ms = float(np.mean(ts)), float(np.mean(tg))
+        rel = float((Ld["y"].float() - yb.float()).norm() / yb.float().norm())
+        sum_ms += t
+        bf16_ms += g_ms
+        wbytes = s.N * s.K // 2 + 2 * s.N * (s.K // s.g)
+        per_layer.append({"layer": s.name, "M": s.M, "K": s.K, "N": s.N, "g": s.g, "w4a16_gemm_ms": round(t, 4),
+                          "bf16_gemm_ms": round(g_ms, 4), "frac_bf16_peak": round(2.0 * s.M * s.N * s.K / (t * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                          "weight_bytes_vs_bf16": round(wbytes / (2.0 * s.N * s.K), 4), "rel_err_vs_bf16_gemm": round(rel, 5)})
+        log(f"{s.name}: w4a16 {t:.3f} ms  bf16 GEMM {g_ms:.3f} ms")
+    ach = total_ops / (sum_ms * 1e-3) / 1e12
+    out = {"metric": "effective TOPS of the W4A16 linear (16-bit activations, 4-bit per-group weights)",
+           "value": round(value, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16 (exact int4 codes as bf16, fp32 accumulate)", "data": "synthetic",
+           "config": {"workload": f"{args.workload}-shaped layers through dirotq_w4a16_gemm, one call per layer per step",
+                      "seed": 0},
+           "speedup_vs_bf16_gemm": round(bf16_ms / ms_per_step, 4),
+           "roofline": {"kernel": "w4a16_gemm_kernel", "bound": "mfma", "dtype": "bf16", "achieved": round(ach, 3),
+                        "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 5),
+                        "avg_launch_ms": round(sum_ms / len(layers), 5), "traffic": None},
+           "layers": per_layer, "cpu_baseline": None}
+    print(json.dumps(out), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -65,6 +139,9 @@ def main() -> int:
                     help="asymmetric activation quantizer (zero-point min, 16 unsigned levels): the *_asym entry points")
     ap.add_argument("--a8", action="store_true",
                     help="8-bit per-token activations against the same 4-bit weights: the *_a8 entry points")
+    ap.add_argument("--w4a16", action="store_true",
+                    help="time dirotq_w4a16_gemm (16-bit activations, 4-bit weights, no rotation) on the workload's "
+                         "layer shapes instead of the W4A4 layer")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise copy of known size (256 MiB read + 256 MiB written), "
                          "the reference the FETCH_SIZE / WRITE_SIZE counters are scaled by")
@@ -91,6 +168,9 @@ def main() -> int:
 
     def dev_bf16(bits):
         return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
+
+    if args.w4a16:
+        return bench_w4a16(args, shapes, B, I, np, torch)
 
     # ---- inputs, resident in HBM before anything is timed ---------------------------
     layers = []
