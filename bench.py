@@ -11,6 +11,7 @@ the dense layers the path replaces.  Prints ONE JSON line.
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -56,7 +57,9 @@ def bench_w4a16(args, shapes, B, I, np, torch) -> int:
         L = I.make_layer(shp)
         W = torch.from_numpy(L.W).to(dev)
         blob = B.prepare_weights(W, torch.eye(shp.K, dtype=torch.float32, device=dev), 0, shp.g)
-        x = torch.from_numpy(np.ascontiguousarray(L.x_bits).view(np.int16)).to(dev).view(torch.bfloat16)
+        if args.tokens:
+            shp = dataclasses.replace(shp, M=min(args.tokens, shp.M))
+        x = torch.from_numpy(np.ascontiguousarray(L.x_bits[:shp.M]).view(np.int16)).to(dev).view(torch.bfloat16)
         layers.append(dict(shape=shp, x=x, blob=blob, Wb=W.to(torch.bfloat16),
                            y=torch.empty((shp.M, shp.N), dtype=torch.bfloat16, device=dev)))
         del W
@@ -106,6 +109,17 @@ def bench_w4a16(args, shapes, B, I, np, torch) -> int:
                           "weight_bytes_vs_bf16": round(wbytes / (2.0 * s.N * s.K), 4), "rel_err_vs_bf16_gemm": round(rel, 5)})
         log(f"{s.name}: w4a16 {t:.3f} ms  bf16 GEMM {g_ms:.3f} ms")
     ach = total_ops / (sum_ms * 1e-3) / 1e12
+    roof = {"kernel": "w4a16_gemm_kernel", "bound": "mfma", "dtype": "bf16", "achieved": round(ach, 3),
+            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 5),
+            "avg_launch_ms": round(sum_ms / len(layers), 5), "traffic": None}
+    if 0 < args.tokens <= 32:
+        # every operand once: packed codes + scales + activations + output
+        nbytes = sum(Ld["shape"].N * Ld["shape"].K // 2 + 2 * Ld["shape"].N * (Ld["shape"].K // Ld["shape"].g) +
+                     2 * Ld["shape"].M * (Ld["shape"].K + Ld["shape"].N) for Ld in layers)
+        gbs = nbytes / (sum_ms * 1e-3) / 1e9
+        roof = {"kernel": "w4a16_skinny_kernel", "bound": "hbm", "achieved": round(gbs, 1), "peak": 8000.0, "unit": "GB/s",
+                "frac": round(gbs / 8000.0, 5), "avg_launch_ms": round(sum_ms / len(layers), 5),
+                "algorithmic_bytes_per_launch": nbytes / len(layers), "traffic": None}
     out = {"metric": "effective TOPS of the W4A16 linear (16-bit activations, 4-bit per-group weights)",
            "value": round(value, 3), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -113,10 +127,7 @@ def bench_w4a16(args, shapes, B, I, np, torch) -> int:
            "config": {"workload": f"{args.workload}-shaped layers through dirotq_w4a16_gemm, one call per layer per step",
                       "seed": 0},
            "speedup_vs_bf16_gemm": round(bf16_ms / ms_per_step, 4),
-           "roofline": {"kernel": "w4a16_gemm_kernel", "bound": "mfma", "dtype": "bf16", "achieved": round(ach, 3),
-                        "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 5),
-                        "avg_launch_ms": round(sum_ms / len(layers), 5), "traffic": None},
-           "layers": per_layer, "cpu_baseline": None}
+           "roofline": roof, "layers": per_layer, "cpu_baseline": None}
     print(json.dumps(out), flush=True)
     return 0
 
@@ -142,6 +153,9 @@ def main() -> int:
     ap.add_argument("--w4a16", action="store_true",
                     help="time dirotq_w4a16_gemm (16-bit activations, 4-bit weights, no rotation) on the workload's "
                          "layer shapes instead of the W4A4 layer")
+    ap.add_argument("--tokens", type=int, default=0,
+                    help="with --w4a16: use only the first TOKENS tokens of each layer's activations (<= 32 takes "
+                         "the few-token kernel, which is bound by the weight stream)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise copy of known size (256 MiB read + 256 MiB written), "
                          "the reference the FETCH_SIZE / WRITE_SIZE counters are scaled by")

@@ -223,6 +223,127 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a16_gemm_kernel(
   gemm_tail<OUT_F32>(acc, smem, nullptr, nullptr, bias, y, M, N, 0, m0, n0, rowA, rowB);
 }
 
+
+// ---- few tokens (M <= 32): every weight is used once, so the kernel is a stream over the packed
+// weights (HBM-bound) and skips LDS for the operands.  One workgroup = 32 output channels; its NW waves
+// split the K axis into NW contiguous runs of scale groups and add their partial sums through LDS in a
+// fixed order.
+// Orientation D[token][n]: the activations are the row operand (tokens padded to 32 by re-reading the
+// last one), a lane owns one output channel, so the group's weight scale is a per-lane scalar.
+// Lane half h holds channels [h GS/2, (h + 1) GS/2) of the group: GS/2 bytes of codes, one load.
+template <int GS, bool OUT_F32, int NW>
+__global__ __launch_bounds__(NW * 64) void w4a16_skinny_kernel(
+    const uint16_t* __restrict__ x, const uint8_t* __restrict__ wq, const uint16_t* __restrict__ sw,
+    const uint16_t* __restrict__ bias, int M, int N, int K, void* __restrict__ y, int sw_shift) {
+  static_assert(GS == 32 || GS == 64, "scale granularity");
+  constexpr int STEPS = GS / 16;          // MFMA steps (16 channels over the lane pair) per group
+  constexpr int CW = STEPS;               // code dwords per lane and group
+  static_assert(NW == 4 || NW == 8, "waves per workgroup");
+  __shared__ float red[NW][16][64];
+  const int t = threadIdx.x, l = t & 63, w = t >> 6, h = l >> 5, c = l & 31;
+  const int n = blockIdx.x * 32 + c, nc = min(n, N - 1);
+  const int mrow = min(c, M - 1);
+  const int nkb = K / GS;
+  const uint8_t* gw = wq + (size_t)nc * (K / 2) + h * (GS / 4);
+  const uint16_t* gx = x + (size_t)mrow * K + h * (GS / 2);
+  const uint16_t* gs = sw + nc;
+
+  f32x16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; v++) acc[v] = 0.0f;
+
+  // A ring of DEPTH group fetches per wave keeps enough bytes in flight to cover the memory latency
+  // (one wave per SIMD is typical for these launches).  The loop is branch-free: a fetch past the end
+  // re-reads the last group and its scale is replaced by zero.
+  constexpr int DEPTH = 4;
+  uint32_t cw[DEPTH][CW];
+  bf16x8 xa[DEPTH][STEPS];
+  uint32_t sc[DEPTH];                      // raw scale bits: nothing is computed on a load until it is used
+  // wave w owns the contiguous run of groups [kb0, kb1): it walks along its 32 weight rows
+  const int per = (nkb + NW - 1) / NW, kb0 = w * per, kb1 = min(kb0 + per, nkb);
+  auto fetch = [&](int u, int kb_raw) {
+    const int kb = min(kb_raw, nkb - 1);
+    if constexpr (CW == 4) {
+      const uint4 v = *(const uint4*)(gw + (size_t)kb * (GS / 2));
+      cw[u][0] = v.x, cw[u][1] = v.y, cw[u][2] = v.z, cw[u][3] = v.w;
+    } else {
+      const uint2 v = *(const uint2*)(gw + (size_t)kb * (GS / 2));
+      cw[u][0] = v.x, cw[u][1] = v.y;
+    }
+#pragma unroll
+    for (int s2 = 0; s2 < STEPS; s2++) xa[u][s2] = *(const bf16x8*)(gx + (size_t)kb * GS + 8 * s2);
+    sc[u] = gs[(size_t)(kb >> sw_shift) * N];
+  };
+  auto block = [&](int u, bool live) {
+    f32x16 z;
+#pragma unroll
+    for (int v = 0; v < 16; v++) z[v] = 0.0f;
+#pragma unroll
+    for (int s2 = 0; s2 < STEPS; s2++) {
+      const uint4 wv = nibbles_to_bf16(cw[u][s2]);
+      z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[u][s2], __builtin_bit_cast(bf16x8, wv), z, 0, 0, 0);
+    }
+    const float sf = f16_bits_to_f32((uint16_t)(live ? sc[u] : 0u));
+#pragma unroll
+    for (int v = 0; v < 16; v++) acc[v] = fmaf(z[v], sf, acc[v]);
+  };
+  // (the scheduling fences keep each refill where it is written: right after the group it replaces)
+#pragma unroll
+  for (int d = 0; d < DEPTH; d++) {
+    fetch(d, kb0 + d);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  for (int kb = kb0; kb < kb1; kb += DEPTH) {
+#pragma unroll
+    for (int d = 0; d < DEPTH; d++) {
+      block(d, kb + d < kb1);
+      __builtin_amdgcn_sched_barrier(0);
+      fetch(d, kb + d + DEPTH);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+#pragma unroll
+  for (int v = 0; v < 16; v++) red[w][v][l] = acc[v];
+  __syncthreads();
+  // wave w finishes 16 / NW accumulator registers (register v holds token 8 (v / 4) + 4 h + v % 4);
+  // partial sums are added in wave order
+  if (n < N) {
+    const float b = bias ? bf16_bits_to_f32(bias[n]) : 0.0f;
+    constexpr int RPW = 16 / NW;
+#pragma unroll
+    for (int e = 0; e < RPW; e++) {
+      const int v = RPW * w + e, m = 8 * (v >> 2) + 4 * h + (v & 3);
+      if (m < M) {
+        float r = red[0][v][l];
+#pragma unroll
+        for (int p = 1; p < NW; p++) r += red[p][v][l];
+        r += b;
+        if (OUT_F32) ((float*)y)[(size_t)m * N + n] = r;
+        else ((uint16_t*)y)[(size_t)m * N + n] = f32_to_bf16_bits(r);
+      }
+    }
+  }
+}
+
+template <int GS, bool OUT_F32>
+static int launch_skinny16(const uint16_t* x, const void* blob, const uint16_t* bias, int M, int N, int K, int g,
+                           void* y, hipStream_t s) {
+  const BlobLayout L = blob_layout(N, K, 0, g);
+  const char* bp = (const char*)blob;
+  const uint8_t* wq = (const uint8_t*)(bp + L.off_codes);
+  const uint16_t* sw = (const uint16_t*)(bp + L.off_sw);
+  const int sw_shift = g == 2 * GS ? 1 : 0;
+  // 8 waves per workgroup when there are few workgroups and enough scale groups to split further
+  if (K / GS >= 16 && (N + 31) / 32 < 256)
+    hipLaunchKernelGGL((w4a16_skinny_kernel<GS, OUT_F32, 8>), dim3((N + 31) / 32), dim3(512), 0, s, x, wq, sw, bias, M,
+                       N, K, y, sw_shift);
+  else
+    hipLaunchKernelGGL((w4a16_skinny_kernel<GS, OUT_F32, 4>), dim3((N + 31) / 32), dim3(256), 0, s, x, wq, sw, bias, M,
+                       N, K, y, sw_shift);
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? DIROTQ_OK : hip_failed(e);
+}
+
 template <int GS, bool OUT_F32>
 static int launch_one16(const uint16_t* x, const void* blob, const uint16_t* bias, int M, int N, int K, int g, void* y,
                         hipStream_t s) {
@@ -248,6 +369,15 @@ static int launch_one16(const uint16_t* x, const void* blob, const uint16_t* bia
 
 int launch_w4a16_gemm(const uint16_t* x, const void* blob, const uint16_t* bias, int M, int N, int K, int g, void* y,
                       int y_dtype, hipStream_t s) {
+  if (M <= 32) {                      // few tokens: the weight stream, not the matrix pipe, is the bound
+    if (g == 32)
+      return y_dtype ? launch_skinny16<32, true>(x, blob, bias, M, N, K, g, y, s)
+                     : launch_skinny16<32, false>(x, blob, bias, M, N, K, g, y, s);
+    if (g == 64 || g == 128)
+      return y_dtype ? launch_skinny16<64, true>(x, blob, bias, M, N, K, g, y, s)
+                     : launch_skinny16<64, false>(x, blob, bias, M, N, K, g, y, s);
+    return DIROTQ_ERR_UNSUPPORTED;
+  }
   if (g == 32)
     return y_dtype ? launch_one16<32, true>(x, blob, bias, M, N, K, g, y, s)
                    : launch_one16<32, false>(x, blob, bias, M, N, K, g, y, s);
