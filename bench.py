@@ -153,6 +153,9 @@ def main() -> int:
     ap.add_argument("--w4a16", action="store_true",
                     help="time dirotq_w4a16_gemm (16-bit activations, 4-bit weights, no rotation) on the workload's "
                          "layer shapes instead of the W4A4 layer")
+    ap.add_argument("--graph", action="store_true",
+                    help="also record one step into a HIP graph and time its replays (graph_ms_per_step); the "
+                         "headline value stays the eager one")
     ap.add_argument("--tokens", type=int, default=0,
                     help="with --w4a16: use only the first TOKENS tokens of each layer's activations (<= 32 takes "
                          "the few-token kernel, which is bound by the weight stream)")
@@ -283,6 +286,23 @@ def main() -> int:
     value = total_ops / (ms_per_step * 1e-3) / 1e12
     log(f"step {ms_per_step:.3f} ms (wall {wall_ms / args.steps:.3f} ms) -> {value:.1f} effective TOPS")
 
+    graph_ms = None
+    if args.graph:
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr):
+            step()
+        for _ in range(args.warmup):
+            gr.replay()
+        torch.cuda.synchronize()
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g0.record()
+        for _ in range(args.steps):
+            gr.replay()
+        g1.record()
+        torch.cuda.synchronize()
+        graph_ms = g0.elapsed_time(g1) / args.steps
+        log(f"graph replay {graph_ms:.4f} ms per step (eager {ms_per_step:.4f} ms)")
+
     # ---- per-kernel timing (HIP events on the launch stream), same launches ------------
     def time_calls(fn, reps):
         fn()
@@ -409,6 +429,7 @@ def main() -> int:
                    "shared_input": bool(args.shared_input)},
         "speedup_vs_bf16_gemm": round(bf16_ms / ms_per_step, 4),
         "bf16_gemm_ms_per_step": round(bf16_ms, 4),
+        "graph_ms_per_step": None if graph_ms is None else round(graph_ms, 4),
         "roofline": {k: (round(v, 5) if isinstance(v, float) else v) for k, v in roofline.items()},
         "kernels": other,
         "layers": per_layer,
