@@ -325,6 +325,175 @@ __global__ __launch_bounds__(NW * 64) void w4a16_skinny_kernel(
   }
 }
 
+
+// ---- very few tokens (M <= 8): the same stream over the weights with the loads fully coalesced.
+// One workgroup (8 waves) = 32 output channels.  K is walked in chunks of 1024 channels: the chunk's codes
+// (32 rows x 512 B), activations (M rows x 2 KB) and scales go through registers into one of two LDS
+// buffers, every thread loading consecutive 16-byte pieces of a row, while the waves multiply the
+// previous chunk (wave w takes scale groups w, w + 8, ...).  LDS rows are padded by 16 bytes so that
+// the 32 lanes of an operand read hit different banks.  Within each run of 8 channels both operands
+// are kept in the order c0 c2 c4 c6 c1 c3 c5 c7 (the activations are permuted once when they are
+// staged), which saves the last round of byte permutes of the weight decode.
+constexpr int FEW_KC = 1024;                     // channels per chunk
+constexpr int FEW_WROW = FEW_KC / 2 + 16;        // bytes per LDS row of codes
+constexpr int FEW_XROW = FEW_KC * 2 + 16;        // bytes per LDS row of activations
+constexpr int FEW_CODES_B = 32 * FEW_WROW;
+constexpr int FEW_X_B = 8 * FEW_XROW;
+constexpr int few_buf_bytes(int gs) { return FEW_CODES_B + FEW_X_B + (FEW_KC / gs) * 32 * 2; }
+
+// 8 sign-magnitude nibbles -> bf16 in the order c0 c2 c4 c6 c1 c3 c5 c7
+__device__ __forceinline__ uint4 nibbles_to_bf16_eo(uint32_t p) {
+  const uint32_t sel_e = p & 0x07070707u, sel_o = (p >> 4) & 0x07070707u;
+  const uint32_t lo_e = __builtin_amdgcn_perm(0xE0C0A080u, 0x40008000u, sel_e);
+  const uint32_t lo_o = __builtin_amdgcn_perm(0xE0C0A080u, 0x40008000u, sel_o);
+  uint32_t hi_e = __builtin_amdgcn_perm(0x40404040u, 0x40403F00u, sel_e);
+  uint32_t hi_o = __builtin_amdgcn_perm(0x40404040u, 0x40403F00u, sel_o);
+  hi_e |= (p & 0x08080808u) << 4;
+  hi_o |= p & 0x80808080u;
+  uint4 r;
+  r.x = __builtin_amdgcn_perm(hi_e, lo_e, 0x05010400u);   // c0, c2
+  r.y = __builtin_amdgcn_perm(hi_e, lo_e, 0x07030602u);   // c4, c6
+  r.z = __builtin_amdgcn_perm(hi_o, lo_o, 0x05010400u);   // c1, c3
+  r.w = __builtin_amdgcn_perm(hi_o, lo_o, 0x07030602u);   // c5, c7
+  return r;
+}
+
+template <int GS, bool OUT_F32>
+__global__ __launch_bounds__(512) void w4a16_few_kernel(
+    const uint16_t* __restrict__ x, const uint8_t* __restrict__ wq, const uint16_t* __restrict__ sw,
+    const uint16_t* __restrict__ bias, int M, int N, int K, void* __restrict__ y, int sw_shift) {
+  static_assert(GS == 32 || GS == 64, "scale granularity");
+  constexpr int STEPS = GS / 16, GPC = FEW_KC / GS, BUF = few_buf_bytes(GS);
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int t = threadIdx.x, l = t & 63, w = t >> 6, h = l >> 5, c = l & 31;
+  const int n0 = blockIdx.x * 32, n = n0 + c;
+  const int mrow = min(c, M - 1);
+  const int nch = (K + FEW_KC - 1) / FEW_KC;
+
+  // staging roles of this thread within a chunk
+  const int crow = t >> 5, cpiece = t & 31;              // codes: rows crow and crow + 16, 16-byte piece cpiece
+  const uint8_t* gc[2];
+#pragma unroll
+  for (int i = 0; i < 2; i++) gc[i] = wq + (size_t)min(n0 + crow + 16 * i, N - 1) * (K / 2) + cpiece * 16;
+  const int xrow[2] = {t >> 7, (t >> 7) + 4};            // activations: token rows t / 128 and t / 128 + 4
+  const int xpiece = t & 127;
+  const uint16_t* gx[2];
+#pragma unroll
+  for (int i = 0; i < 2; i++) gx[i] = x + (size_t)min(xrow[i], M - 1) * K + xpiece * 8;
+  constexpr int SPT = GPC / 16;                          // scales per thread: groups t / 32 (+ 16), channel t % 32
+  const int sgrp = t >> 5;
+  const uint16_t* gsc = sw + min(n0 + (t & 31), N - 1);
+
+  uint4 rc[2], rx[2];
+  uint32_t rs[SPT] = {};
+  auto gload = [&](int ch) {
+    const int k0 = ch * FEW_KC;
+    const bool cok = k0 + cpiece * 32 < K, xok = k0 + xpiece * 8 < K;
+#pragma unroll
+    for (int i = 0; i < 2; i++) {
+      rc[i] = cok ? *(const uint4*)(gc[i] + k0 / 2) : make_uint4(0, 0, 0, 0);
+      rx[i] = (xok && xrow[i] < M) ? *(const uint4*)(gx[i] + k0) : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < SPT; i++) {
+      const int j = ch * GPC + sgrp + 16 * i;
+      if (j < K / GS) rs[i] = gsc[(size_t)(j >> sw_shift) * N];
+    }
+  };
+  auto sstore = [&](int buf) {
+    unsigned char* sb = smem + buf * BUF;
+#pragma unroll
+    for (int i = 0; i < 2; i++) {
+      *(uint4*)(sb + (crow + 16 * i) * FEW_WROW + cpiece * 16) = rc[i];
+      uint4 v;                                            // c0c1 c2c3 c4c5 c6c7 -> c0c2 c4c6 c1c3 c5c7
+      v.x = __builtin_amdgcn_perm(rx[i].y, rx[i].x, 0x05040100u);
+      v.y = __builtin_amdgcn_perm(rx[i].w, rx[i].z, 0x05040100u);
+      v.z = __builtin_amdgcn_perm(rx[i].y, rx[i].x, 0x07060302u);
+      v.w = __builtin_amdgcn_perm(rx[i].w, rx[i].z, 0x07060302u);
+      *(uint4*)(sb + FEW_CODES_B + xrow[i] * FEW_XROW + xpiece * 16) = v;
+    }
+#pragma unroll
+    for (int i = 0; i < SPT; i++)
+      ((uint16_t*)(sb + FEW_CODES_B + FEW_X_B))[(sgrp + 16 * i) * 32 + (t & 31)] = (uint16_t)rs[i];
+  };
+
+  f32x16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; v++) acc[v] = 0.0f;
+
+  gload(0);
+  sstore(0);
+  __syncthreads();
+  for (int ch = 0; ch < nch; ch++) {
+    const bool more = ch + 1 < nch;
+    if (more) gload(ch + 1);                              // in flight while this chunk is multiplied
+    const unsigned char* sb = smem + (ch & 1) * BUF;
+    const int groups = min(GPC, (K - ch * FEW_KC) / GS);
+    for (int gi = w; gi < groups; gi += 8) {
+      uint32_t cw[STEPS];
+      if constexpr (GS == 64) {
+        const uint4 v = *(const uint4*)(sb + c * FEW_WROW + gi * 32 + h * 16);
+        cw[0] = v.x, cw[1] = v.y, cw[2] = v.z, cw[3] = v.w;
+      } else {
+        const uint2 v = *(const uint2*)(sb + c * FEW_WROW + gi * 16 + h * 8);
+        cw[0] = v.x, cw[1] = v.y;
+      }
+      const unsigned char* xs = sb + FEW_CODES_B + mrow * FEW_XROW + (gi * GS + h * (GS / 2)) * 2;
+      f32x16 z;
+#pragma unroll
+      for (int v = 0; v < 16; v++) z[v] = 0.0f;
+#pragma unroll
+      for (int s2 = 0; s2 < STEPS; s2++) {
+        const bf16x8 xa = *(const bf16x8*)(xs + s2 * 16);
+        const uint4 wv = nibbles_to_bf16_eo(cw[s2]);
+        z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, __builtin_bit_cast(bf16x8, wv), z, 0, 0, 0);
+      }
+      const float sf = f16_bits_to_f32(((const uint16_t*)(sb + FEW_CODES_B + FEW_X_B))[gi * 32 + c]);
+      // tokens 0..7 live in accumulator registers 0..3 (token 4 h + v); the others are padding
+#pragma unroll
+      for (int v = 0; v < 4; v++) acc[v] = fmaf(z[v], sf, acc[v]);
+    }
+    if (more) sstore((ch + 1) & 1);
+    __syncthreads();
+  }
+  // partial sums of the 8 waves, added in wave order: red[wave][register][lane]
+  float* red = (float*)smem;
+#pragma unroll
+  for (int v = 0; v < 4; v++) red[(w * 4 + v) * 64 + l] = acc[v];
+  __syncthreads();
+  if (w < 4 && n < N) {
+    const int m = 4 * h + w;
+    if (m < M) {
+      float r = red[w * 64 + l];
+#pragma unroll
+      for (int p2 = 1; p2 < 8; p2++) r += red[(p2 * 4 + w) * 64 + l];
+      if (bias) r += bf16_bits_to_f32(bias[n]);
+      if (OUT_F32) ((float*)y)[(size_t)m * N + n] = r;
+      else ((uint16_t*)y)[(size_t)m * N + n] = f32_to_bf16_bits(r);
+    }
+  }
+}
+
+template <int GS, bool OUT_F32>
+static int launch_few16(const uint16_t* x, const void* blob, const uint16_t* bias, int M, int N, int K, int g, void* y,
+                        hipStream_t s) {
+  const BlobLayout L = blob_layout(N, K, 0, g);
+  const char* bp = (const char*)blob;
+  constexpr int SMEM = 2 * few_buf_bytes(GS);
+  static std::atomic<bool> attr_done{false};
+  if (!attr_done.load(std::memory_order_acquire)) {
+    hipError_t e = hipFuncSetAttribute((const void*)w4a16_few_kernel<GS, OUT_F32>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
+    if (e != hipSuccess) return hip_failed(e);
+    attr_done.store(true, std::memory_order_release);
+  }
+  hipLaunchKernelGGL((w4a16_few_kernel<GS, OUT_F32>), dim3((N + 31) / 32), dim3(512), SMEM, s, x,
+                     (const uint8_t*)(bp + L.off_codes), (const uint16_t*)(bp + L.off_sw), bias, M, N, K, y,
+                     g == 2 * GS ? 1 : 0);
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? DIROTQ_OK : hip_failed(e);
+}
+
 template <int GS, bool OUT_F32>
 static int launch_skinny16(const uint16_t* x, const void* blob, const uint16_t* bias, int M, int N, int K, int g,
                            void* y, hipStream_t s) {
@@ -369,6 +538,15 @@ static int launch_one16(const uint16_t* x, const void* blob, const uint16_t* bia
 
 int launch_w4a16_gemm(const uint16_t* x, const void* blob, const uint16_t* bias, int M, int N, int K, int g, void* y,
                       int y_dtype, hipStream_t s) {
+  if (M <= 8) {                       // a handful of tokens: activations fit in LDS next to the weight chunks
+    if (g == 32)
+      return y_dtype ? launch_few16<32, true>(x, blob, bias, M, N, K, g, y, s)
+                     : launch_few16<32, false>(x, blob, bias, M, N, K, g, y, s);
+    if (g == 64 || g == 128)
+      return y_dtype ? launch_few16<64, true>(x, blob, bias, M, N, K, g, y, s)
+                     : launch_few16<64, false>(x, blob, bias, M, N, K, g, y, s);
+    return DIROTQ_ERR_UNSUPPORTED;
+  }
   if (M <= 32) {                      // few tokens: the weight stream, not the matrix pipe, is the bound
     if (g == 32)
       return y_dtype ? launch_skinny16<32, true>(x, blob, bias, M, N, K, g, y, s)

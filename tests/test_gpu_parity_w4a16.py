@@ -29,7 +29,8 @@ def _blob(qw, sw, N, K, g):
                                      (70, 40, 96, 32), (33, 130, 32, 32), (129, 257, 1152, 64),
                                      (1, 200, 256, 32), (8, 136, 448, 64), (32, 129, 384, 128), (3, 40, 96, 32),
                                      (17, 33, 32, 32), (2, 31, 64, 64), (32, 3072, 3072, 64),
-                                     (4, 100, 1152, 32), (16, 70, 1152, 128)])
+                                     (4, 100, 1152, 32), (16, 70, 1152, 128),
+                                     (8, 100, 2080, 32), (5, 64, 1024, 64), (7, 33, 3200, 64), (1, 40, 2048, 128)])
 def test_w4a16_integer_exact(M, N, K, g):
     """Unit scales, small-integer activations: an integer matrix product below 2^24, exact in fp32
     (every code value, odd 32-channel counts, every group size, ragged tiles; M <= 32 takes the
