@@ -163,29 +163,34 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a8_gemm_kernel(
     const int nst = (KL + BK8 - 1) / BK8;
     uint4 rw, rt[2];
     uint16_t rs[GPS];
-    auto gload = [&](int st) {
-      rw = *(const uint4*)(gw + min(st * (BK8 / 2), wlast));
+    // one stage = 4 pieces (weights, two activation rows, scales); piece p is reloaded for stage s+2 right
+    // after it has been unpacked into LDS for stage s+1, so a global load has a whole stage to complete
+    auto gload_piece = [&](int st, int p) {
+      if (p == 0) {
+        rw = *(const uint4*)(gw + min(st * (BK8 / 2), wlast));
+      } else if (p < 3) {
+        rt[p - 1] = *(const uint4*)(gt[p - 1] + min(st * BK8, tlast));
+      } else {
 #pragma unroll
-      for (int i = 0; i < 2; i++) rt[i] = *(const uint4*)(gt[i] + min(st * BK8, tlast));
-#pragma unroll
-      for (int jj = 0; jj < GPS; jj++) {
-        const int j = st * GPS + jj;
-        const uint16_t v = gs[(size_t)(min(j, G - 1) >> sw_shift) * N];
-        rs[jj] = (uint16_t)(v & (j < G ? 0xFFFFu : 0u));
+        for (int jj = 0; jj < GPS; jj++) {
+          const int j = st * GPS + jj;
+          const uint16_t v = gs[(size_t)(min(j, G - 1) >> sw_shift) * N];
+          rs[jj] = (uint16_t)(v & (j < G ? 0xFFFFu : 0u));
+        }
       }
     };
-    auto sstore = [&](int buf) {
+    auto sstore_piece = [&](int buf, int p) {
       unsigned char* sb = smem + buf * STAGE8;
-      uint4 e, o;
-      unpack8_sm(rw.x, e.x, o.x);
-      unpack8_sm(rw.y, e.y, o.y);
-      unpack8_sm(rw.z, e.z, o.z);
-      unpack8_sm(rw.w, e.w, o.w);
-      *(uint4*)(sb + w_off_bytes(wrow, 2 * wblk)) = e;
-      *(uint4*)(sb + w_off_bytes(wrow, 2 * wblk + 1)) = o;
-#pragma unroll
-      for (int i = 0; i < 2; i++) {
-        const int row = trow + 64 * i;
+      if (p == 0) {
+        uint4 e, o;
+        unpack8_sm(rw.x, e.x, o.x);
+        unpack8_sm(rw.y, e.y, o.y);
+        unpack8_sm(rw.z, e.z, o.z);
+        unpack8_sm(rw.w, e.w, o.w);
+        *(uint4*)(sb + w_off_bytes(wrow, 2 * wblk)) = e;
+        *(uint4*)(sb + w_off_bytes(wrow, 2 * wblk + 1)) = o;
+      } else if (p < 3) {
+        const int i = p - 1, row = trow + 64 * i;
         uint4 a, b;                                              // planes: [s 0000 aaa] and [s 000 bbbb]
         a.x = (rt[i].x & 0x80808080u) | ((rt[i].x >> 4) & 0x07070707u);
         a.y = (rt[i].y & 0x80808080u) | ((rt[i].y >> 4) & 0x07070707u);
@@ -197,8 +202,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a8_gemm_kernel(
         b.w = rt[i].w & 0x8F8F8F8Fu;
         *(uint4*)(sb + W_BYTES + tile_off_bytes(row, tchk)) = a;
         *(uint4*)(sb + W_BYTES + tile_off_bytes(row, 4 + tchk)) = b;
-      }
-      if (t < TN) {
+      } else if (t < TN) {
         uint2* sdst = (uint2*)(smem + SCALE8_OFF + buf * SBUF);
 #pragma unroll
         for (int jj = 0; jj < GPS; jj++) sdst[jj * TN + t] = make_uint2(rs[jj], 0u);
@@ -235,12 +239,17 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a8_gemm_kernel(
     const int scale_b = h ? 127 : 131;    // E8M0: k-block 0 (the a-plane, lanes 0..31 hold its scale) x 2^4
     const int scale_a = 127;
 
-    gload(0);
-    sstore(0);
-    gload(min(1, nst - 1));
+#pragma unroll
+    for (int p = 0; p < 4; p++) gload_piece(0, p);
+#pragma unroll
+    for (int p = 0; p < 4; p++) {
+      sstore_piece(0, p);
+      gload_piece(min(1, nst - 1), p);
+    }
     __syncthreads();
     for (int st = 0; st < nst; st++) {
       const int buf = st & 1;
+      const int st2 = min(st + 2, nst - 1);     // past the end: harmless re-load, never used
       const unsigned char* sb = smem + buf * STAGE8;
       const unsigned char* ssb = smem + buf * sbufstep;
       f32x16 I[2], P[2];
@@ -279,32 +288,53 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a8_gemm_kernel(
         for (int v = 0; v < 16; v++) acc[i][j][v] = fmaf(I[slot][v], P[slot][v], acc[i][j][v]);
         asm volatile("" : "+v"(acc[i][j]));
       };
+      // the next stage's unpack work is spread over the tile sweeps of this stage
+      constexpr int NSTEP = GPS * 4;
+      auto stage_piece = [&](int step) {
+        if ((step + 1) % (NSTEP / 4) == 0) {
+          const int p = (step + 1) / (NSTEP / 4) - 1;
+          sstore_piece(buf ^ 1, p);
+          gload_piece(st2, p);
+        }
+      };
+      // one pipeline step = the MFMAs of the next tile interleaved with the fma sweep of the current one
+      auto interleave = [&](bool valu_first) {
+        constexpr int NM = MPG + 1, PER = 16 / NM;
+        if (valu_first) __builtin_amdgcn_sched_group_barrier(0x002, PER, 0);
+#pragma unroll
+        for (int q = 0; q < NM; q++) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
+          __builtin_amdgcn_sched_group_barrier(0x002, PER, 0);    // PER VALU instructions
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      };
       load_ops(0);
       issue(0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int jj = 0; jj < GPS; jj++) {
+        const bool more = jj + 1 < GPS;
         issue(0, 1, 1);
         sweep(0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
+        stage_piece(jj * 4 + 0);
+        interleave(false);
         issue(1, 0, 0);
         sweep(0, 1, 1);
-        __builtin_amdgcn_sched_barrier(0);
+        stage_piece(jj * 4 + 1);
+        interleave(false);
         issue(1, 1, 1);
         sweep(1, 0, 0);
-        if (jj == GPS - 1) {                      // the next stage: registers -> LDS, then reload for stage st+2
-          sstore(buf ^ 1);
-          gload(min(st + 2, nst - 1));
-        }
-        __builtin_amdgcn_sched_barrier(0);
+        stage_piece(jj * 4 + 2);
+        interleave(false);
         asm volatile("" ::: "memory");
-        if (jj + 1 < GPS) {
+        if (more) {
           load_ops(jj + 1);
           __builtin_amdgcn_sched_barrier(0);
           issue(0, 0, 0);
         }
         sweep(1, 1, 1);
-        __builtin_amdgcn_sched_barrier(0);
+        stage_piece(jj * 4 + 3);
+        interleave(true);
       }
       __syncthreads();
     }
