@@ -13,7 +13,7 @@ from paper_2605_16732_amd import inputs as I
 
 from gpu_util import (check_output, dev, dev_bf16, host_bf16_bits, host_f16, import_blob)
 
-pytestmark = pytest.mark.gpu
+gpu = pytest.mark.gpu
 
 
 def _say(msg):
@@ -45,7 +45,7 @@ def unpack_i8(b: np.ndarray) -> np.ndarray:
     return np.where(nat & 0x80, -mag, mag).astype(np.int8)
 
 
-def test_pack_roundtrip_host():
+def test_pack_roundtrip_host():        # no GPU needed: checks the helpers above
     q = np.random.default_rng(0).integers(-127, 128, size=(3, 96)).astype(np.int8)
     np.testing.assert_array_equal(unpack_i8(pack_i8(q)), q)
     assert pack_i8(np.arange(32)[None, :])[0, :4].tolist() == [0, 2, 4, 6]
@@ -74,6 +74,7 @@ def _signed_perm(K, seed):
     (300, 256, 64, False), (300, 256, 32, True), (129, 384, 0, True), (1, 128, 32, False),
     (257, 1152, 64, True), (64, 96, 96, True), (130, 448, 64, True), (700, 3072, 128, True), (40, 96, 64, True),
 ])
+@gpu
 def test_rotate_quantize_a8_exact_with_permutation_basis(M, K, r, perm):
     """With Q a (signed) permutation the rotation is exact, so the bf16 part, the INT8 codes and the
     per-token scales must equal the oracle's bit for bit (all tile shapes of the launcher are hit)."""
@@ -91,6 +92,7 @@ def test_rotate_quantize_a8_exact_with_permutation_basis(M, K, r, perm):
     np.testing.assert_array_equal(qx_g, qx_r)
 
 
+@gpu
 def test_rotate_quantize_a8_hand_rows():
     """The hand-worked tokens of tests/golden/quantizer_int8_cases.txt laid into rows (zero padded)."""
     K = 64
@@ -113,6 +115,7 @@ def test_rotate_quantize_a8_hand_rows():
 # ------------------------------------------------------------------ GEMM
 @pytest.mark.parametrize("M,N,K,g", [(130, 200, 256, 32), (257, 136, 448, 64), (64, 129, 384, 128), (5, 8, 64, 32),
                                      (70, 40, 96, 32), (33, 130, 32, 32), (129, 257, 1152, 64)])
+@gpu
 def test_w4a8_integer_exact(M, N, K, g):
     """Unit scales: y = sum_k q_x q_w with |q_x| <= 127, |q_w| <= 7 is an integer below 2^24, exact in
     fp32 (covers the extreme codes, odd 32-channel counts and every group size)."""
@@ -134,6 +137,7 @@ def test_w4a8_integer_exact(M, N, K, g):
     np.testing.assert_array_equal(y.cpu().numpy(), want)
 
 
+@gpu
 def test_w4a8_one_hot_codes_address_every_channel():
     """A single nonzero activation code per token picks out one weight code: any slip in the
     even/odd byte order or in the plane split shows up as a wrong element."""
@@ -155,6 +159,7 @@ def test_w4a8_one_hot_codes_address_every_channel():
     (200, 136, 320, 64, 64, True), (130, 129, 288, 32, 32, False), (64, 64, 256, 128, 128, True),
     (300, 264, 1152, 64, 64, False), (140, 72, 3072, 0, 64, False), (77, 50, 160, 64, 32, True),
 ])
+@gpu
 def test_w4a8_matches_oracle_on_identical_inputs(M, N, K, r, g, use_bias):
     """Same inputs on both sides: only the fp32 accumulation order differs (1e-5 of the largest output)."""
     _say(f"w4a8 vs oracle M={M} N={N} K={K} r={r} g={g} bias={use_bias}")
@@ -237,6 +242,7 @@ def _end_to_end_a8(shape, rows=None):
          f"{stats['scale_flips']}, out row-rel {row_err:.2e} max-rel {max_err:.2e}")
 
 
+@gpu
 def test_end_to_end_a8_small_and_ragged():
     _end_to_end_a8(I.SMALL)
     _end_to_end_a8(I.LayerShape("ragged_8", 333, 384, 200, 0, 32, 4, 7, 0))
@@ -244,18 +250,21 @@ def test_end_to_end_a8_small_and_ragged():
     _end_to_end_a8(I.LayerShape("odd32_8", 100, 224, 72, 64, 32, 4, 7, 2))
 
 
+@gpu
 def test_end_to_end_a8_flux_fc1_full_launch_sampled_rows():
     shp = I.FLUX[2]
     rows = np.sort(np.random.default_rng(41).choice(shp.M, size=48, replace=False))
     _end_to_end_a8(shp, rows=rows)
 
 
+@gpu
 def test_end_to_end_a8_flux_fc2_full_launch_sampled_rows():
     shp = I.FLUX[3]
     rows = np.sort(np.random.default_rng(42).choice(shp.M, size=24, replace=False))
     _end_to_end_a8(shp, rows=rows)
 
 
+@gpu
 def test_a8_rank_equals_K_and_empty():
     shp = I.LayerShape("allhigh_8", 150, 256, 96, 256, 32, 4, 7, 2)
     L = I.make_layer(shp)
