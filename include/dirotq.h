@@ -32,6 +32,8 @@
  *    detected on the host before anything is enqueued; nothing is written then.
  *  - Supported shapes: M >= 0 (M == 0 is a no-op), N >= 1, K a multiple of 32,
  *    0 <= r <= K with r a multiple of 32, g in {32, 64, 128}, (K - r) % g == 0.
+ *    Upper limits: M, N <= 2^24, K <= 2^20, ceil(M/128) * ceil(N/128) <= 2^30; element
+ *    offsets are 64-bit, so M*K, M*N and N*K may exceed 2^31.
  *  - INT4 packing (activations): byte i of a row holds channel 2i of the 4-bit part
  *    in bits 0-3 and channel 2i+1 in bits 4-7.  A nibble is the code q in [-7, 7] in
  *    sign-magnitude form: bit 3 = sign, bits 0-2 = |q|; zero is always 0x0.
@@ -50,7 +52,7 @@ extern "C" {
 typedef enum {
   DIROTQ_OK = 0,
   DIROTQ_ERR_NULL = -1,        /* a required pointer is NULL */
-  DIROTQ_ERR_SHAPE = -2,       /* M<0, N<1, K<32, K%32, r<0, r>K, r%32, g not in {32,64,128}, (K-r)%g */
+  DIROTQ_ERR_SHAPE = -2,       /* M<0, N<1, K<32, K%32, r<0, r>K, r%32, g not in {32,64,128}, (K-r)%g, too large */
   DIROTQ_ERR_ALIGN = -3,       /* a device pointer is not 16-byte aligned */
   DIROTQ_ERR_WORKSPACE = -4,   /* workspace / scratch / blob buffer too small */
   DIROTQ_ERR_UNSUPPORTED = -5, /* valid request this build does not implement */

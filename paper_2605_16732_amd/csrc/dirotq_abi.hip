@@ -18,6 +18,8 @@ int check_shape(long M, long N, long K, long r, long g) {
   if (!(g == 32 || g == 64 || g == 128)) return DIROTQ_ERR_SHAPE;
   if ((K - r) % g != 0) return DIROTQ_ERR_SHAPE;
   if (M > (1 << 24) || N > (1 << 24)) return DIROTQ_ERR_SHAPE;
+  // the GEMM grids are one workgroup per 128 x 128 output tile, indexed with 32-bit integers
+  if (((M + 127) / 128) * ((N + 127) / 128) > (1L << 30)) return DIROTQ_ERR_SHAPE;
   return DIROTQ_OK;
 }
 

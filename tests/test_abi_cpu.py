@@ -61,6 +61,8 @@ def test_size_queries():
     (8, 128, 0, 48),     # g not in {32,64,128}
     (8, 128, 32, 64),    # (K - r) % g
     (8, 0, 0, 32),       # K < 32
+    ((1 << 24) + 1, 64, 0, 32),   # N beyond the limit
+    (8, (1 << 20) + 32, 0, 32),   # K beyond the limit
 ])
 def test_bad_shapes_are_rejected(N, K, r, g):
     out = ctypes.c_size_t(7)
@@ -132,6 +134,18 @@ def test_argument_errors_before_any_launch():
     # M == 0 is a valid no-op and launches nothing
     assert L.dirotq_rotate_quantize(a, a, 0, 64, 0, 32, None, a, a, None) == B.OK
     assert L.dirotq_w4a4_gemm(None, a, a, a, None, 0, 8, 64, 0, 32, a, 0, None) == B.OK
+
+
+def test_output_tilings_beyond_32_bit_grids_are_rejected():
+    L = B.lib()
+    a = 0x1000
+    big = 1 << 24                  # 131072 x 131072 tiles of 128 x 128 would overflow the grid index
+    assert L.dirotq_w4a4_gemm(None, a, a, a, None, big, big, 64, 0, 32, a, 0, None) == B.ERR_SHAPE
+    assert L.dirotq_linear(a, a, a, None, big, big, 64, 0, 32, a, a, 1 << 62, None) == B.ERR_SHAPE
+    assert L.dirotq_w4a16_gemm(a, a, None, big, big, 64, 32, a, 0, None) == B.ERR_SHAPE
+    out = ctypes.c_size_t(0)
+    assert L.dirotq_workspace_bytes(big, 1 << 20, 0, 32, ctypes.byref(out)) == B.OK     # sizes are 64-bit
+    assert out.value > (1 << 42)
 
 
 def test_error_type_carries_message():
