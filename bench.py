@@ -117,7 +117,7 @@ def bench_w4a16(args, shapes, B, I, np, torch) -> int:
         nbytes = sum(Ld["shape"].N * Ld["shape"].K // 2 + 2 * Ld["shape"].N * (Ld["shape"].K // Ld["shape"].g) +
                      2 * Ld["shape"].M * (Ld["shape"].K + Ld["shape"].N) for Ld in layers)
         gbs = nbytes / (sum_ms * 1e-3) / 1e9
-        roof = {"kernel": "w4a16_few_kernel" if args.tokens <= 8 else "w4a16_skinny_kernel", "bound": "hbm", "achieved": round(gbs, 1), "peak": 8000.0, "unit": "GB/s",
+        roof = {"kernel": "w4a16_few_kernel", "bound": "hbm", "achieved": round(gbs, 1), "peak": 8000.0, "unit": "GB/s",
                 "frac": round(gbs / 8000.0, 5), "avg_launch_ms": round(sum_ms / len(layers), 5),
                 "algorithmic_bytes_per_launch": nbytes / len(layers), "traffic": None}
     out = {"metric": "effective TOPS of the W4A16 linear (16-bit activations, 4-bit per-group weights)",

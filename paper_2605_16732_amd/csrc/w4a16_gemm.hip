@@ -224,122 +224,30 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a16_gemm_kernel(
 }
 
 
-// ---- few tokens (M <= 32): every weight is used once, so the kernel is a stream over the packed
-// weights (HBM-bound) and skips LDS for the operands.  One workgroup = 32 output channels; its NW waves
-// split the K axis into NW contiguous runs of scale groups and add their partial sums through LDS in a
-// fixed order.
-// Orientation D[token][n]: the activations are the row operand (tokens padded to 32 by re-reading the
-// last one), a lane owns one output channel, so the group's weight scale is a per-lane scalar.
-// Lane half h holds channels [h GS/2, (h + 1) GS/2) of the group: GS/2 bytes of codes, one load.
-template <int GS, bool OUT_F32, int NW>
-__global__ __launch_bounds__(NW * 64) void w4a16_skinny_kernel(
-    const uint16_t* __restrict__ x, const uint8_t* __restrict__ wq, const uint16_t* __restrict__ sw,
-    const uint16_t* __restrict__ bias, int M, int N, int K, void* __restrict__ y, int sw_shift) {
-  static_assert(GS == 32 || GS == 64, "scale granularity");
-  constexpr int STEPS = GS / 16;          // MFMA steps (16 channels over the lane pair) per group
-  constexpr int CW = STEPS;               // code dwords per lane and group
-  static_assert(NW == 4 || NW == 8, "waves per workgroup");
-  __shared__ float red[NW][16][64];
-  const int t = threadIdx.x, l = t & 63, w = t >> 6, h = l >> 5, c = l & 31;
-  const int n = blockIdx.x * 32 + c, nc = min(n, N - 1);
-  const int mrow = min(c, M - 1);
-  const int nkb = K / GS;
-  const uint8_t* gw = wq + (size_t)nc * (K / 2) + h * (GS / 4);
-  const uint16_t* gx = x + (size_t)mrow * K + h * (GS / 2);
-  const uint16_t* gs = sw + nc;
-
-  f32x16 acc;
-#pragma unroll
-  for (int v = 0; v < 16; v++) acc[v] = 0.0f;
-
-  // A ring of DEPTH group fetches per wave keeps enough bytes in flight to cover the memory latency
-  // (one wave per SIMD is typical for these launches).  The loop is branch-free: a fetch past the end
-  // re-reads the last group and its scale is replaced by zero.
-  constexpr int DEPTH = 4;
-  uint32_t cw[DEPTH][CW];
-  bf16x8 xa[DEPTH][STEPS];
-  uint32_t sc[DEPTH];                      // raw scale bits: nothing is computed on a load until it is used
-  // wave w owns the contiguous run of groups [kb0, kb1): it walks along its 32 weight rows
-  const int per = (nkb + NW - 1) / NW, kb0 = w * per, kb1 = min(kb0 + per, nkb);
-  auto fetch = [&](int u, int kb_raw) {
-    const int kb = min(kb_raw, nkb - 1);
-    if constexpr (CW == 4) {
-      const uint4 v = *(const uint4*)(gw + (size_t)kb * (GS / 2));
-      cw[u][0] = v.x, cw[u][1] = v.y, cw[u][2] = v.z, cw[u][3] = v.w;
-    } else {
-      const uint2 v = *(const uint2*)(gw + (size_t)kb * (GS / 2));
-      cw[u][0] = v.x, cw[u][1] = v.y;
-    }
-#pragma unroll
-    for (int s2 = 0; s2 < STEPS; s2++) xa[u][s2] = *(const bf16x8*)(gx + (size_t)kb * GS + 8 * s2);
-    sc[u] = gs[(size_t)(kb >> sw_shift) * N];
-  };
-  auto block = [&](int u, bool live) {
-    f32x16 z;
-#pragma unroll
-    for (int v = 0; v < 16; v++) z[v] = 0.0f;
-#pragma unroll
-    for (int s2 = 0; s2 < STEPS; s2++) {
-      const uint4 wv = nibbles_to_bf16(cw[u][s2]);
-      z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[u][s2], __builtin_bit_cast(bf16x8, wv), z, 0, 0, 0);
-    }
-    const float sf = f16_bits_to_f32((uint16_t)(live ? sc[u] : 0u));
-#pragma unroll
-    for (int v = 0; v < 16; v++) acc[v] = fmaf(z[v], sf, acc[v]);
-  };
-  // (the scheduling fences keep each refill where it is written: right after the group it replaces)
-#pragma unroll
-  for (int d = 0; d < DEPTH; d++) {
-    fetch(d, kb0 + d);
-    __builtin_amdgcn_sched_barrier(0);
-  }
-  for (int kb = kb0; kb < kb1; kb += DEPTH) {
-#pragma unroll
-    for (int d = 0; d < DEPTH; d++) {
-      block(d, kb + d < kb1);
-      __builtin_amdgcn_sched_barrier(0);
-      fetch(d, kb + d + DEPTH);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  }
-#pragma unroll
-  for (int v = 0; v < 16; v++) red[w][v][l] = acc[v];
-  __syncthreads();
-  // wave w finishes 16 / NW accumulator registers (register v holds token 8 (v / 4) + 4 h + v % 4);
-  // partial sums are added in wave order
-  if (n < N) {
-    const float b = bias ? bf16_bits_to_f32(bias[n]) : 0.0f;
-    constexpr int RPW = 16 / NW;
-#pragma unroll
-    for (int e = 0; e < RPW; e++) {
-      const int v = RPW * w + e, m = 8 * (v >> 2) + 4 * h + (v & 3);
-      if (m < M) {
-        float r = red[0][v][l];
-#pragma unroll
-        for (int p = 1; p < NW; p++) r += red[p][v][l];
-        r += b;
-        if (OUT_F32) ((float*)y)[(size_t)m * N + n] = r;
-        else ((uint16_t*)y)[(size_t)m * N + n] = f32_to_bf16_bits(r);
-      }
-    }
-  }
-}
-
-
-// ---- very few tokens (M <= 8): the same stream over the weights with the loads fully coalesced.
-// One workgroup (8 waves) = 32 output channels.  K is walked in chunks of 1024 channels: the chunk's codes
-// (32 rows x 512 B), activations (M rows x 2 KB) and scales go through registers into one of two LDS
-// buffers, every thread loading consecutive 16-byte pieces of a row, while the waves multiply the
-// previous chunk (wave w takes scale groups w, w + 8, ...).  LDS rows are padded by 16 bytes so that
-// the 32 lanes of an operand read hit different banks.  Within each run of 8 channels both operands
-// are kept in the order c0 c2 c4 c6 c1 c3 c5 c7 (the activations are permuted once when they are
-// staged), which saves the last round of byte permutes of the weight decode.
-constexpr int FEW_KC = 1024;                     // channels per chunk
-constexpr int FEW_WROW = FEW_KC / 2 + 16;        // bytes per LDS row of codes
-constexpr int FEW_XROW = FEW_KC * 2 + 16;        // bytes per LDS row of activations
-constexpr int FEW_CODES_B = 32 * FEW_WROW;
-constexpr int FEW_X_B = 8 * FEW_XROW;
-constexpr int few_buf_bytes(int gs) { return FEW_CODES_B + FEW_X_B + (FEW_KC / gs) * 32 * 2; }
+// ---- few tokens (M <= 32): every weight is used once, so the kernel is a stream over the packed weights
+// (HBM-bound).  One workgroup (8 waves) = 32 output channels.  K is walked in chunks of KC channels (1024
+// for up to 8 tokens, 512 for up to 32): the chunk's codes (32 rows x KC/2 B), activations (MT rows x 2 KC B)
+// and scales go through registers into one of two LDS buffers, every thread loading consecutive 16-byte
+// pieces of a row, while the waves multiply the previous chunk (wave w takes scale groups w, w + 8, ...).
+// Orientation D[token][n]: the activations are the row operand of the 32x32x16 MFMA (tokens padded to 32 by
+// re-reading the last one), a lane owns one output channel, so the group's weight scale is a per-lane
+// scalar; lane half h holds channels [h GS/2, (h + 1) GS/2) of the group.  LDS rows are padded by 16 bytes
+// so that the 32 lanes of an operand read hit different banks.  Within each run of 8 channels both
+// operands are kept in the order c0 c2 c4 c6 c1 c3 c5 c7 (the activations are permuted once when they
+// are staged), which saves the last round of byte permutes of the weight decode.  The 8 waves' partial
+// sums are added through LDS in wave order.
+template <int MT>
+struct Few {
+  static_assert(MT == 8 || MT == 32, "token capacity");
+  static constexpr int KC = MT == 8 ? 1024 : 512;   // channels per chunk
+  static constexpr int WROW = KC / 2 + 16;          // bytes per LDS row of codes
+  static constexpr int XROW = KC * 2 + 16;          // bytes per LDS row of activations
+  static constexpr int CODES_B = 32 * WROW;
+  static constexpr int X_B = MT * XROW;
+  static constexpr int NV = MT / 2;                 // accumulator registers that hold real tokens (of 16)
+  static constexpr int buf_bytes(int gs) { return CODES_B + X_B + (KC / gs) * 32 * 2; }
+  static constexpr int smem_bytes(int gs) { return 2 * buf_bytes(gs) > 8 * NV * 256 ? 2 * buf_bytes(gs) : 8 * NV * 256; }
+};
 
 // 8 sign-magnitude nibbles -> bf16 in the order c0 c2 c4 c6 c1 c3 c5 c7
 __device__ __forceinline__ uint4 nibbles_to_bf16_eo(uint32_t p) {
@@ -358,63 +266,74 @@ __device__ __forceinline__ uint4 nibbles_to_bf16_eo(uint32_t p) {
   return r;
 }
 
-template <int GS, bool OUT_F32>
+template <int GS, bool OUT_F32, int MT>
 __global__ __launch_bounds__(512) void w4a16_few_kernel(
     const uint16_t* __restrict__ x, const uint8_t* __restrict__ wq, const uint16_t* __restrict__ sw,
     const uint16_t* __restrict__ bias, int M, int N, int K, void* __restrict__ y, int sw_shift) {
   static_assert(GS == 32 || GS == 64, "scale granularity");
-  constexpr int STEPS = GS / 16, GPC = FEW_KC / GS, BUF = few_buf_bytes(GS);
+  using F = Few<MT>;
+  constexpr int KC = F::KC, STEPS = GS / 16, GPC = KC / GS, BUF = F::buf_bytes(GS), NV = F::NV;
+  constexpr int CPT = KC / 512;                 // 16-byte code pieces per thread and chunk (32 rows x KC/32 pieces)
+  constexpr int XPT = MT * (KC / 8) / 512;      // 16-byte activation pieces per thread and chunk
+  constexpr int SPT = (GPC * 32 + 511) / 512;   // scales per thread and chunk
   extern __shared__ __align__(16) unsigned char smem[];
   const int t = threadIdx.x, l = t & 63, w = t >> 6, h = l >> 5, c = l & 31;
   const int n0 = blockIdx.x * 32, n = n0 + c;
   const int mrow = min(c, M - 1);
-  const int nch = (K + FEW_KC - 1) / FEW_KC;
+  const int nch = (K + KC - 1) / KC;
 
-  // staging roles of this thread within a chunk
-  const int crow = t >> 5, cpiece = t & 31;              // codes: rows crow and crow + 16, 16-byte piece cpiece
-  const uint8_t* gc[2];
+  // staging roles of this thread within a chunk: piece index t + 512 i over (row, 16-byte piece of the row)
+  int crow[CPT], cpiece[CPT], xrow[XPT], xpiece[XPT];
+  const uint8_t* gc[CPT];
+  const uint16_t* gx[XPT];
 #pragma unroll
-  for (int i = 0; i < 2; i++) gc[i] = wq + (size_t)min(n0 + crow + 16 * i, N - 1) * (K / 2) + cpiece * 16;
-  const int xrow[2] = {t >> 7, (t >> 7) + 4};            // activations: token rows t / 128 and t / 128 + 4
-  const int xpiece = t & 127;
-  const uint16_t* gx[2];
+  for (int i = 0; i < CPT; i++) {
+    const int idx = t + 512 * i;
+    crow[i] = idx / (KC / 32), cpiece[i] = idx % (KC / 32);
+    gc[i] = wq + (size_t)min(n0 + crow[i], N - 1) * (K / 2) + cpiece[i] * 16;
+  }
 #pragma unroll
-  for (int i = 0; i < 2; i++) gx[i] = x + (size_t)min(xrow[i], M - 1) * K + xpiece * 8;
-  constexpr int SPT = GPC / 16;                          // scales per thread: groups t / 32 (+ 16), channel t % 32
-  const int sgrp = t >> 5;
-  const uint16_t* gsc = sw + min(n0 + (t & 31), N - 1);
+  for (int i = 0; i < XPT; i++) {
+    const int idx = t + 512 * i;
+    xrow[i] = idx / (KC / 8), xpiece[i] = idx % (KC / 8);
+    gx[i] = x + (size_t)min(xrow[i], M - 1) * K + xpiece[i] * 8;
+  }
+  const uint16_t* gsc = sw + min(n0 + (t & 31), N - 1);       // scale (group (t + 512 i) / 32, channel t % 32)
 
-  uint4 rc[2], rx[2];
+  uint4 rc[CPT], rx[XPT];
   uint32_t rs[SPT] = {};
   auto gload = [&](int ch) {
-    const int k0 = ch * FEW_KC;
-    const bool cok = k0 + cpiece * 32 < K, xok = k0 + xpiece * 8 < K;
+    const int k0 = ch * KC;
 #pragma unroll
-    for (int i = 0; i < 2; i++) {
-      rc[i] = cok ? *(const uint4*)(gc[i] + k0 / 2) : make_uint4(0, 0, 0, 0);
-      rx[i] = (xok && xrow[i] < M) ? *(const uint4*)(gx[i] + k0) : make_uint4(0, 0, 0, 0);
-    }
+    for (int i = 0; i < CPT; i++)
+      rc[i] = k0 + cpiece[i] * 32 < K ? *(const uint4*)(gc[i] + k0 / 2) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < XPT; i++)
+      rx[i] = (k0 + xpiece[i] * 8 < K && xrow[i] < M) ? *(const uint4*)(gx[i] + k0) : make_uint4(0, 0, 0, 0);
 #pragma unroll
     for (int i = 0; i < SPT; i++) {
-      const int j = ch * GPC + sgrp + 16 * i;
-      if (j < K / GS) rs[i] = gsc[(size_t)(j >> sw_shift) * N];
+      const int sg = (t + 512 * i) >> 5, j = ch * GPC + sg;
+      if (sg < GPC && j < K / GS) rs[i] = gsc[(size_t)(j >> sw_shift) * N];
     }
   };
   auto sstore = [&](int buf) {
     unsigned char* sb = smem + buf * BUF;
 #pragma unroll
-    for (int i = 0; i < 2; i++) {
-      *(uint4*)(sb + (crow + 16 * i) * FEW_WROW + cpiece * 16) = rc[i];
+    for (int i = 0; i < CPT; i++) *(uint4*)(sb + crow[i] * F::WROW + cpiece[i] * 16) = rc[i];
+#pragma unroll
+    for (int i = 0; i < XPT; i++) {
       uint4 v;                                            // c0c1 c2c3 c4c5 c6c7 -> c0c2 c4c6 c1c3 c5c7
       v.x = __builtin_amdgcn_perm(rx[i].y, rx[i].x, 0x05040100u);
       v.y = __builtin_amdgcn_perm(rx[i].w, rx[i].z, 0x05040100u);
       v.z = __builtin_amdgcn_perm(rx[i].y, rx[i].x, 0x07060302u);
       v.w = __builtin_amdgcn_perm(rx[i].w, rx[i].z, 0x07060302u);
-      *(uint4*)(sb + FEW_CODES_B + xrow[i] * FEW_XROW + xpiece * 16) = v;
+      *(uint4*)(sb + F::CODES_B + xrow[i] * F::XROW + xpiece[i] * 16) = v;
     }
 #pragma unroll
-    for (int i = 0; i < SPT; i++)
-      ((uint16_t*)(sb + FEW_CODES_B + FEW_X_B))[(sgrp + 16 * i) * 32 + (t & 31)] = (uint16_t)rs[i];
+    for (int i = 0; i < SPT; i++) {
+      const int sg = (t + 512 * i) >> 5;
+      if (sg < GPC) ((uint16_t*)(sb + F::CODES_B + F::X_B))[sg * 32 + (t & 31)] = (uint16_t)rs[i];
+    }
   };
 
   f32x16 acc;
@@ -428,17 +347,17 @@ __global__ __launch_bounds__(512) void w4a16_few_kernel(
     const bool more = ch + 1 < nch;
     if (more) gload(ch + 1);                              // in flight while this chunk is multiplied
     const unsigned char* sb = smem + (ch & 1) * BUF;
-    const int groups = min(GPC, (K - ch * FEW_KC) / GS);
+    const int groups = min(GPC, (K - ch * KC) / GS);
     for (int gi = w; gi < groups; gi += 8) {
       uint32_t cw[STEPS];
       if constexpr (GS == 64) {
-        const uint4 v = *(const uint4*)(sb + c * FEW_WROW + gi * 32 + h * 16);
+        const uint4 v = *(const uint4*)(sb + c * F::WROW + gi * 32 + h * 16);
         cw[0] = v.x, cw[1] = v.y, cw[2] = v.z, cw[3] = v.w;
       } else {
-        const uint2 v = *(const uint2*)(sb + c * FEW_WROW + gi * 16 + h * 8);
+        const uint2 v = *(const uint2*)(sb + c * F::WROW + gi * 16 + h * 8);
         cw[0] = v.x, cw[1] = v.y;
       }
-      const unsigned char* xs = sb + FEW_CODES_B + mrow * FEW_XROW + (gi * GS + h * (GS / 2)) * 2;
+      const unsigned char* xs = sb + F::CODES_B + mrow * F::XROW + (gi * GS + h * (GS / 2)) * 2;
       f32x16 z;
 #pragma unroll
       for (int v = 0; v < 16; v++) z[v] = 0.0f;
@@ -448,10 +367,10 @@ __global__ __launch_bounds__(512) void w4a16_few_kernel(
         const uint4 wv = nibbles_to_bf16_eo(cw[s2]);
         z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, __builtin_bit_cast(bf16x8, wv), z, 0, 0, 0);
       }
-      const float sf = f16_bits_to_f32(((const uint16_t*)(sb + FEW_CODES_B + FEW_X_B))[gi * 32 + c]);
-      // tokens 0..7 live in accumulator registers 0..3 (token 4 h + v); the others are padding
+      const float sf = f16_bits_to_f32(((const uint16_t*)(sb + F::CODES_B + F::X_B))[gi * 32 + c]);
+      // accumulator register v holds token 8 (v / 4) + 4 h + v % 4: the first NV cover tokens 0 .. MT-1
 #pragma unroll
-      for (int v = 0; v < 4; v++) acc[v] = fmaf(z[v], sf, acc[v]);
+      for (int v = 0; v < NV; v++) acc[v] = fmaf(z[v], sf, acc[v]);
     }
     if (more) sstore((ch + 1) & 1);
     __syncthreads();
@@ -459,56 +378,42 @@ __global__ __launch_bounds__(512) void w4a16_few_kernel(
   // partial sums of the 8 waves, added in wave order: red[wave][register][lane]
   float* red = (float*)smem;
 #pragma unroll
-  for (int v = 0; v < 4; v++) red[(w * 4 + v) * 64 + l] = acc[v];
+  for (int v = 0; v < NV; v++) red[(w * NV + v) * 64 + l] = acc[v];
   __syncthreads();
-  if (w < 4 && n < N) {
-    const int m = 4 * h + w;
-    if (m < M) {
-      float r = red[w * 64 + l];
+  constexpr int RPW = (NV + 7) / 8;                       // registers finished by each wave
+  if (n < N) {
+    const float b = bias ? bf16_bits_to_f32(bias[n]) : 0.0f;
 #pragma unroll
-      for (int p2 = 1; p2 < 8; p2++) r += red[(p2 * 4 + w) * 64 + l];
-      if (bias) r += bf16_bits_to_f32(bias[n]);
-      if (OUT_F32) ((float*)y)[(size_t)m * N + n] = r;
-      else ((uint16_t*)y)[(size_t)m * N + n] = f32_to_bf16_bits(r);
+    for (int e = 0; e < RPW; e++) {
+      const int v = w * RPW + e, m = 8 * (v >> 2) + 4 * h + (v & 3);
+      if (v < NV && m < M) {
+        float r = red[v * 64 + l];
+#pragma unroll
+        for (int p2 = 1; p2 < 8; p2++) r += red[(p2 * NV + v) * 64 + l];
+        r += b;
+        if (OUT_F32) ((float*)y)[(size_t)m * N + n] = r;
+        else ((uint16_t*)y)[(size_t)m * N + n] = f32_to_bf16_bits(r);
+      }
     }
   }
 }
 
-template <int GS, bool OUT_F32>
+template <int GS, bool OUT_F32, int MT>
 static int launch_few16(const uint16_t* x, const void* blob, const uint16_t* bias, int M, int N, int K, int g, void* y,
                         hipStream_t s) {
   const BlobLayout L = blob_layout(N, K, 0, g);
   const char* bp = (const char*)blob;
-  constexpr int SMEM = 2 * few_buf_bytes(GS);
+  constexpr int SMEM = Few<MT>::smem_bytes(GS);
   static std::atomic<bool> attr_done{false};
   if (!attr_done.load(std::memory_order_acquire)) {
-    hipError_t e = hipFuncSetAttribute((const void*)w4a16_few_kernel<GS, OUT_F32>,
+    hipError_t e = hipFuncSetAttribute((const void*)w4a16_few_kernel<GS, OUT_F32, MT>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, SMEM);
     if (e != hipSuccess) return hip_failed(e);
     attr_done.store(true, std::memory_order_release);
   }
-  hipLaunchKernelGGL((w4a16_few_kernel<GS, OUT_F32>), dim3((N + 31) / 32), dim3(512), SMEM, s, x,
+  hipLaunchKernelGGL((w4a16_few_kernel<GS, OUT_F32, MT>), dim3((N + 31) / 32), dim3(512), SMEM, s, x,
                      (const uint8_t*)(bp + L.off_codes), (const uint16_t*)(bp + L.off_sw), bias, M, N, K, y,
                      g == 2 * GS ? 1 : 0);
-  hipError_t e = hipGetLastError();
-  return e == hipSuccess ? DIROTQ_OK : hip_failed(e);
-}
-
-template <int GS, bool OUT_F32>
-static int launch_skinny16(const uint16_t* x, const void* blob, const uint16_t* bias, int M, int N, int K, int g,
-                           void* y, hipStream_t s) {
-  const BlobLayout L = blob_layout(N, K, 0, g);
-  const char* bp = (const char*)blob;
-  const uint8_t* wq = (const uint8_t*)(bp + L.off_codes);
-  const uint16_t* sw = (const uint16_t*)(bp + L.off_sw);
-  const int sw_shift = g == 2 * GS ? 1 : 0;
-  // 8 waves per workgroup when there are few workgroups and enough scale groups to split further
-  if (K / GS >= 16 && (N + 31) / 32 < 256)
-    hipLaunchKernelGGL((w4a16_skinny_kernel<GS, OUT_F32, 8>), dim3((N + 31) / 32), dim3(512), 0, s, x, wq, sw, bias, M,
-                       N, K, y, sw_shift);
-  else
-    hipLaunchKernelGGL((w4a16_skinny_kernel<GS, OUT_F32, 4>), dim3((N + 31) / 32), dim3(256), 0, s, x, wq, sw, bias, M,
-                       N, K, y, sw_shift);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? DIROTQ_OK : hip_failed(e);
 }
@@ -538,23 +443,20 @@ static int launch_one16(const uint16_t* x, const void* blob, const uint16_t* bia
 
 int launch_w4a16_gemm(const uint16_t* x, const void* blob, const uint16_t* bias, int M, int N, int K, int g, void* y,
                       int y_dtype, hipStream_t s) {
-  if (M <= 8) {                       // a handful of tokens: activations fit in LDS next to the weight chunks
-    if (g == 32)
-      return y_dtype ? launch_few16<32, true>(x, blob, bias, M, N, K, g, y, s)
-                     : launch_few16<32, false>(x, blob, bias, M, N, K, g, y, s);
-    if (g == 64 || g == 128)
-      return y_dtype ? launch_few16<64, true>(x, blob, bias, M, N, K, g, y, s)
-                     : launch_few16<64, false>(x, blob, bias, M, N, K, g, y, s);
-    return DIROTQ_ERR_UNSUPPORTED;
-  }
   if (M <= 32) {                      // few tokens: the weight stream, not the matrix pipe, is the bound
-    if (g == 32)
-      return y_dtype ? launch_skinny16<32, true>(x, blob, bias, M, N, K, g, y, s)
-                     : launch_skinny16<32, false>(x, blob, bias, M, N, K, g, y, s);
-    if (g == 64 || g == 128)
-      return y_dtype ? launch_skinny16<64, true>(x, blob, bias, M, N, K, g, y, s)
-                     : launch_skinny16<64, false>(x, blob, bias, M, N, K, g, y, s);
-    return DIROTQ_ERR_UNSUPPORTED;
+    const int gs = g == 32 ? 32 : 64;
+    if (M <= 8) {
+      if (gs == 32)
+        return y_dtype ? launch_few16<32, true, 8>(x, blob, bias, M, N, K, g, y, s)
+                       : launch_few16<32, false, 8>(x, blob, bias, M, N, K, g, y, s);
+      return y_dtype ? launch_few16<64, true, 8>(x, blob, bias, M, N, K, g, y, s)
+                     : launch_few16<64, false, 8>(x, blob, bias, M, N, K, g, y, s);
+    }
+    if (gs == 32)
+      return y_dtype ? launch_few16<32, true, 32>(x, blob, bias, M, N, K, g, y, s)
+                     : launch_few16<32, false, 32>(x, blob, bias, M, N, K, g, y, s);
+    return y_dtype ? launch_few16<64, true, 32>(x, blob, bias, M, N, K, g, y, s)
+                   : launch_few16<64, false, 32>(x, blob, bias, M, N, K, g, y, s);
   }
   if (g == 32)
     return y_dtype ? launch_one16<32, true>(x, blob, bias, M, N, K, g, y, s)
