@@ -209,8 +209,9 @@ __global__ __launch_bounds__(NTHREADS, 2) void w4a8_gemm_kernel(
       }
     };
 
-    // per-lane LDS addresses.  MFMA step c (0..3) of a stage covers channels 16 (2c' + h) .. of ...:
-    // lane half h takes chunk 2 * step_in_stage + h of the weight row and of both activation planes
+    // per-lane LDS addresses.  MFMA step s2 (0 or 1) of a stage covers its 32-channel block s2:
+    // lane half h takes 16-byte chunk 2 s2 + h (even channels for h = 0, odd ones for h = 1) of the
+    // weight row and of both activation planes (a zero magnitude with the sign bit set is fp8 -0)
     const int wswz = ((l & 31) >> 2) & 3, tswz = ((l & 31) >> 1) & 7;
     int adW[2][2], adTa[2][2], adTb[2][2];
 #pragma unroll
