@@ -310,3 +310,43 @@ def test_int8_against_pure_python_sequence_and_bounds():
     bound = s.astype(np.float64) / 2 * (1 + 2.0 ** -20) + 127 * np.abs(s.astype(np.float64) - amax / 127)
     assert np.all(np.abs(deq - v) <= bound[:, None] + 1e-30)
     assert np.all(np.abs(q).max(1) >= 126)
+
+
+# --------------------------------------------------------------------------
+# symmetries the quantizer equation implies (hold exactly in the fixed fp32 sequence)
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("which", ["int4", "int8"])
+def test_sign_power_of_two_and_permutation_symmetries(which):
+    """Q(-v) = -Q(v); Q(2^k v) has the same codes and the scale times 2^k (every step of the
+    sequence commutes with an exact power-of-two factor while the stored fp16 scale stays a normal
+    number: the exponents below keep it between 2^-14 and 65504); permuting the channels of a group
+    permutes its codes and leaves the scale alone."""
+    rng = np.random.default_rng(77)
+    g = 16
+    v = (rng.standard_normal((64, g)) * rng.lognormal(0, 1, size=(64, 1))).astype(np.float32)
+    quant = (lambda a: O.quantize_groups(a, g)) if which == "int4" else O.quantize_tokens_int8
+    q, s = quant(v)
+    qn, sn = quant(-v)
+    np.testing.assert_array_equal(qn, -q)
+    np.testing.assert_array_equal(sn.view(np.uint16), s.view(np.uint16))
+    assert float(s.astype(np.float32).min()) * 2.0 ** -2 >= 2.0 ** -14
+    for k in (-2, -1, 3, 9):
+        qk, sk = quant((v * np.float32(2.0 ** k)).astype(np.float32))
+        np.testing.assert_array_equal(qk, q)
+        np.testing.assert_array_equal(sk.astype(np.float64).ravel(), s.astype(np.float64).ravel() * 2.0 ** k)
+    perm = rng.permutation(g)
+    qp, sp = quant(np.ascontiguousarray(v[:, perm]))
+    np.testing.assert_array_equal(qp, q[:, perm])
+    np.testing.assert_array_equal(sp.view(np.uint16), s.view(np.uint16))
+
+
+def test_asym_sign_flip_mirrors_the_codes():
+    """Negating a group swaps min and max: codes become 15 - q only where the stored zero-point and
+    scale are exact, so the test uses a dyadic grid (values k / 8, range a multiple of 15 / 8)."""
+    g = 8
+    base = np.array([[0, 15, 1, 7, 8, 14, 3, 12]], np.float32) / np.float32(8.0) - np.float32(0.5)
+    q, s, z = O.quantize_groups_asym(base, g)
+    qn, sn, zn = O.quantize_groups_asym(-base, g)
+    np.testing.assert_array_equal(qn, 15 - q)
+    assert float(sn[0, 0]) == float(s[0, 0]) == 0.125
+    assert float(z[0, 0]) == -0.5 and float(zn[0, 0]) == -(15 / 8 - 0.5)
