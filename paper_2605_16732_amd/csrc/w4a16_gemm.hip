@@ -443,20 +443,40 @@ static int launch_one16(const uint16_t* x, const void* blob, const uint16_t* bia
 
 int launch_w4a16_gemm(const uint16_t* x, const void* blob, const uint16_t* bias, int M, int N, int K, int g, void* y,
                       int y_dtype, hipStream_t s) {
-  if (M <= 32) {                      // few tokens: the weight stream, not the matrix pipe, is the bound
-    const int gs = g == 32 ? 32 : 64;
-    if (M <= 8) {
+  const int gs = g == 32 ? 32 : 64;
+  auto few = [&](const uint16_t* xs, void* ys, int Ms) -> int {   // up to 32 tokens
+    if (Ms <= 8) {
       if (gs == 32)
-        return y_dtype ? launch_few16<32, true, 8>(x, blob, bias, M, N, K, g, y, s)
-                       : launch_few16<32, false, 8>(x, blob, bias, M, N, K, g, y, s);
-      return y_dtype ? launch_few16<64, true, 8>(x, blob, bias, M, N, K, g, y, s)
-                     : launch_few16<64, false, 8>(x, blob, bias, M, N, K, g, y, s);
+        return y_dtype ? launch_few16<32, true, 8>(xs, blob, bias, Ms, N, K, g, ys, s)
+                       : launch_few16<32, false, 8>(xs, blob, bias, Ms, N, K, g, ys, s);
+      return y_dtype ? launch_few16<64, true, 8>(xs, blob, bias, Ms, N, K, g, ys, s)
+                     : launch_few16<64, false, 8>(xs, blob, bias, Ms, N, K, g, ys, s);
     }
     if (gs == 32)
-      return y_dtype ? launch_few16<32, true, 32>(x, blob, bias, M, N, K, g, y, s)
-                     : launch_few16<32, false, 32>(x, blob, bias, M, N, K, g, y, s);
-    return y_dtype ? launch_few16<64, true, 32>(x, blob, bias, M, N, K, g, y, s)
-                   : launch_few16<64, false, 32>(x, blob, bias, M, N, K, g, y, s);
+      return y_dtype ? launch_few16<32, true, 32>(xs, blob, bias, Ms, N, K, g, ys, s)
+                     : launch_few16<32, false, 32>(xs, blob, bias, Ms, N, K, g, ys, s);
+    return y_dtype ? launch_few16<64, true, 32>(xs, blob, bias, Ms, N, K, g, ys, s)
+                   : launch_few16<64, false, 32>(xs, blob, bias, Ms, N, K, g, ys, s);
+  };
+  // few tokens: the weight stream, not the matrix pipe, is the bound
+  if (M <= 32) return few(x, y, M);
+  // A few hundred tokens leave the 128 x 128 tiling with less than one round of workgroups, each walking
+  // all of K: there it is faster to stream the weights once per slice of 32 tokens.  Rough costs in
+  // microseconds from measurements on the FLUX-shaped layers: a slice streams N K / 2 bytes at about
+  // 1.2 TB/s plus 5 us; a round of tiles takes 1.23 us per 64-channel stage.
+  {
+    const int slices = (M + 31) / 32;
+    const long tiles = (long)((M + TM - 1) / TM) * ((N + TN - 1) / TN);
+    const double t_few = slices * ((double)N * K / 2 / 1.2e6 + 5.0);
+    const double t_tiles = (K / 64.0) * 1.23 * (double)((tiles + 511) / 512);
+    if (slices <= 16 && t_few < t_tiles) {
+      const size_t ybytes = y_dtype ? 4 : 2;
+      for (int i = 0; i < slices; i++) {
+        const int st = few(x + (size_t)i * 32 * K, (char*)y + (size_t)i * 32 * N * ybytes, min(32, M - 32 * i));
+        if (st) return st;
+      }
+      return DIROTQ_OK;
+    }
   }
   if (g == 32)
     return y_dtype ? launch_one16<32, true>(x, blob, bias, M, N, K, g, y, s)

@@ -30,11 +30,12 @@ def _blob(qw, sw, N, K, g):
                                      (1, 200, 256, 32), (8, 136, 448, 64), (32, 129, 384, 128), (3, 40, 96, 32),
                                      (17, 33, 32, 32), (2, 31, 64, 64), (32, 3072, 3072, 64),
                                      (4, 100, 1152, 32), (16, 70, 1152, 128),
-                                     (8, 100, 2080, 32), (5, 64, 1024, 64), (7, 33, 3200, 64), (1, 40, 2048, 128)])
+                                     (8, 100, 2080, 32), (5, 64, 1024, 64), (7, 33, 3200, 64), (1, 40, 2048, 128),
+                                     (64, 200, 1152, 64), (100, 136, 3072, 32), (257, 40, 4096, 128)])
 def test_w4a16_integer_exact(M, N, K, g):
     """Unit scales, small-integer activations: an integer matrix product below 2^24, exact in fp32
     (every code value, odd 32-channel counts, every group size, ragged tiles; M <= 32 takes the
-    few-token kernel)."""
+    few-token kernel, a few hundred tokens with a long K run as slices of 32 through it)."""
     _say(f"w4a16 integer M={M} N={N} K={K} g={g}")
     rng = np.random.default_rng(51)
     x = rng.integers(-100, 101, size=(M, K)).astype(np.float32)
@@ -63,6 +64,7 @@ def test_w4a16_one_hot_activations_read_back_every_weight():
     (200, 136, 320, 64, True), (130, 129, 288, 32, False), (64, 64, 256, 128, True),
     (300, 264, 1152, 64, False), (140, 72, 3072, 64, False), (77, 50, 160, 32, True),
     (1, 136, 320, 64, True), (4, 129, 288, 32, False), (32, 64, 256, 128, True), (2, 1000, 3072, 64, True),
+    (100, 136, 3072, 32, True), (70, 260, 2048, 64, False),
 ])
 def test_w4a16_matches_oracle(M, N, K, g, use_bias):
     """Same inputs on both sides: only the order of the fp32 additions differs."""
