@@ -56,7 +56,8 @@ typedef enum {
   DIROTQ_ERR_ALIGN = -3,       /* a device pointer is not 16-byte aligned */
   DIROTQ_ERR_WORKSPACE = -4,   /* workspace / scratch / blob buffer too small */
   DIROTQ_ERR_UNSUPPORTED = -5, /* valid request this build does not implement */
-  DIROTQ_ERR_HIP = -6          /* a HIP call failed; see dirotq_last_hip_error() */
+  DIROTQ_ERR_HIP = -6,         /* a HIP call failed; see dirotq_last_hip_error() */
+  DIROTQ_ERR_STATIC_LIMIT = -7 /* dirotq_linear_static: intermediates exceed its fixed scratch */
 } dirotq_status;
 
 /* Static description of a status code (never freed; host). */
@@ -148,6 +149,23 @@ int dirotq_w4a4_gemm(const uint16_t* xh_bf16, const uint8_t* xl_packed, const ui
 int dirotq_linear(const uint16_t* x_bf16, const uint16_t* Qt_bf16, const void* blob,
                   const uint16_t* bias_bf16, int M, int N, int K, int r, int g,
                   uint16_t* y_bf16 /*out*/, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * dirotq_linear for callers that cannot allocate or pass device memory for intermediates
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc):
+ * the same two kernels, with x_h, packed x_l and s_x kept in a fixed 64 MiB array in device
+ * memory that belongs to the library (one copy per GPU, held until the process ends).  The
+ * call allocates and frees nothing.  DIROTQ_STATIC_SCRATCH_BYTES bounds what
+ * dirotq_workspace_bytes(M, K, r, g) may return (FLUX-shaped fc2, M = 4608, K = 12288:
+ * 31.2 MiB); a larger request returns DIROTQ_ERR_STATIC_LIMIT and enqueues nothing.  All
+ * calls on one GPU share the array: calls that may overlap in time (different streams,
+ * different host threads) race on it, and so does a dirotq_linear_static still running when
+ * another is enqueued on another stream.  Results are bit-identical to dirotq_linear.
+ */
+#define DIROTQ_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+int dirotq_linear_static(const uint16_t* x_bf16, const uint16_t* Qt_bf16, const void* blob,
+                         const uint16_t* bias_bf16, int M, int N, int K, int r, int g,
+                         uint16_t* y_bf16 /*out*/, void* stream);
 
 /*
  * Several layers that read the same activations (fused QKV next to the MLP's first

@@ -17,6 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libdirotq.so")
 
 OK = 0
 ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_HIP = -1, -2, -3, -4, -5, -6
+ERR_STATIC_LIMIT = -7
+STATIC_SCRATCH_BYTES = 64 << 20
 
 _c_int, _c_size_t, _c_void_p = ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p
 _size_p = ctypes.POINTER(ctypes.c_size_t)
@@ -35,6 +37,7 @@ SIGNATURES = {
     "dirotq_rotate_quantize": (_c_int, [_c_void_p, _c_void_p] + [_c_int] * 4 + [_c_void_p] * 4),
     "dirotq_w4a4_gemm": (_c_int, [_c_void_p] * 5 + [_c_int] * 5 + [_c_void_p, _c_int, _c_void_p]),
     "dirotq_linear": (_c_int, [_c_void_p] * 4 + [_c_int] * 5 + [_c_void_p, _c_void_p, _c_size_t, _c_void_p]),
+    "dirotq_linear_static": (_c_int, [_c_void_p] * 4 + [_c_int] * 5 + [_c_void_p, _c_void_p]),
     "dirotq_linear_shared": (_c_int, [_c_void_p, _c_void_p, _c_int] + [_c_void_p] * 4 + [_c_int] * 4 + [_c_void_p, _c_size_t, _c_void_p]),
     "dirotq_rotate_quantize_asym": (_c_int, [_c_void_p, _c_void_p] + [_c_int] * 4 + [_c_void_p] * 5),
     "dirotq_w4a4_gemm_asym": (_c_int, [_c_void_p] * 6 + [_c_int] * 5 + [_c_void_p, _c_int, _c_void_p]),
@@ -189,6 +192,15 @@ def linear(x, Qt, blob, N, r, g, bias=None, workspace=None, out=None):
     _check(lib().dirotq_linear(_ptr(x), _ptr(Qt), _ptr(blob), _ptr(bias), M, N, K, r, g, _ptr(y),
                                _ptr(workspace), workspace.numel(), _stream()), "dirotq_linear")
     return y
+
+
+def linear_static(x, Qt, blob, N, r, g, out, bias=None):
+    """dirotq_linear_static: intermediates live in the library's fixed device array; `out` is
+    required so that this wrapper allocates nothing either."""
+    M, K = x.shape
+    _check(lib().dirotq_linear_static(_ptr(x), _ptr(Qt), _ptr(blob), _ptr(bias), M, N, K, r, g, _ptr(out),
+                                      _stream()), "dirotq_linear_static")
+    return out
 
 
 def rotate_quantize_asym(x, Qt, r, g, out=None):

@@ -1,8 +1,37 @@
 // C-ABI entry points of libdirotq: argument validation, size queries, error
 // reporting.  All checks run on the host before anything is enqueued.
+#include <mutex>
+
 #include "dirotq_internal.h"
 
 namespace dirotq {
+
+// Intermediates of dirotq_linear_static (x_h, packed x_l, s_x of one call): a fixed array in
+// device memory, one copy per GPU the library runs on, held until the process ends.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Device address of `scratch` on the current GPU.  In host code the array's name is only a
+// handle for the runtime: the address is asked for once per device and kept.
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices] = {};
+static int static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_failed(e);
+  if (dev < 0 || dev >= kMaxDevices) return DIROTQ_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_failed(e);
+    if (!p) return DIROTQ_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return DIROTQ_OK;
+}
 
 static thread_local int g_last_hip_error = 0;
 
@@ -39,6 +68,8 @@ const char* dirotq_strerror(int status) {
     case DIROTQ_ERR_WORKSPACE: return "workspace or scratch buffer too small";
     case DIROTQ_ERR_UNSUPPORTED: return "request not supported by this build";
     case DIROTQ_ERR_HIP: return "a HIP call failed (see dirotq_last_hip_error)";
+    case DIROTQ_ERR_STATIC_LIMIT:
+      return "intermediates exceed the 64 MiB static scratch of dirotq_linear_static: use dirotq_linear";
     default: return "unknown status";
   }
 }
@@ -160,6 +191,33 @@ int dirotq_linear(const uint16_t* x_bf16, const uint16_t* Qt_bf16, const void* b
   uint16_t* sx = (uint16_t*)(ws + L.off_sx);
   RqOut o;
   o.xh = xh, o.xl = xl, o.sx = sx;
+  st = launch_rotate_quantize(x_bf16, Qt_bf16, M, K, r, g, o, (hipStream_t)stream);
+  if (st) return st;
+  return launch_w4a4_gemm(xh, xl, sx, nullptr, blob, bias_bf16, M, N, K, r, g, y_bf16, 0, (hipStream_t)stream);
+}
+
+int dirotq_linear_static(const uint16_t* x_bf16, const uint16_t* Qt_bf16, const void* blob,
+                         const uint16_t* bias_bf16, int M, int N, int K, int r, int g, uint16_t* y_bf16,
+                         void* stream) {
+  int st = check_shape(M, N, K, r, g);
+  if (st) return st;
+  if (M == 0) return DIROTQ_OK;
+  if (!x_bf16 || !Qt_bf16 || !blob || !y_bf16) return DIROTQ_ERR_NULL;
+  if (misaligned(x_bf16) || misaligned(Qt_bf16) || misaligned(blob) || misaligned(bias_bf16) || misaligned(y_bf16))
+    return DIROTQ_ERR_ALIGN;
+  const WorkspaceLayout L = workspace_layout(M, K, r, g);
+  if (L.bytes > kStaticScratchBytes) return DIROTQ_ERR_STATIC_LIMIT;
+  void* base = nullptr;
+  st = static_scratch(&base);
+  if (st) return st;
+  char* ws = (char*)base;
+  uint16_t* xh = (uint16_t*)(ws + L.off_xh);
+  uint8_t* xl = (uint8_t*)(ws + L.off_xl);
+  uint16_t* sx = (uint16_t*)(ws + L.off_sx);
+  RqOut o;
+  o.xh = xh, o.xl = xl, o.sx = sx;
+  // every byte of the intermediates that the GEMM reads is written by the rotation kernel of
+  // this call, so nothing of the previous call's contents has to be cleared
   st = launch_rotate_quantize(x_bf16, Qt_bf16, M, K, r, g, o, (hipStream_t)stream);
   if (st) return st;
   return launch_w4a4_gemm(xh, xl, sx, nullptr, blob, bias_bf16, M, N, K, r, g, y_bf16, 0, (hipStream_t)stream);

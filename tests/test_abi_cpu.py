@@ -30,8 +30,8 @@ def test_every_declared_symbol_is_exported_and_bound():
 def test_strerror():
     L = B.lib()
     assert L.dirotq_strerror(0) == b"ok"
-    seen = {L.dirotq_strerror(s) for s in range(-6, 1)}
-    assert len(seen) == 7
+    seen = {L.dirotq_strerror(s) for s in range(-7, 1)}
+    assert len(seen) == 8
     assert L.dirotq_last_hip_error() == 0
 
 
@@ -98,6 +98,15 @@ def test_argument_errors_before_any_launch():
     assert L.dirotq_rotate_quantize_asym(a, a, 0, 64, 0, 32, None, a, a, a, None) == B.OK
     assert L.dirotq_w4a4_gemm_asym(None, a, a, a, a, None, 0, 8, 64, 0, 32, a, 0, None) == B.OK
     assert L.dirotq_linear_asym(a, a, a, None, 0, 8, 64, 0, 32, a, a, 0, None) == B.OK
+    # entry point that keeps its intermediates in the library's fixed device array
+    assert L.dirotq_linear_static(a, a, a, None, 4, 8, 48, 0, 32, a, None) == B.ERR_SHAPE
+    assert L.dirotq_linear_static(a, a, None, None, 4, 8, 64, 0, 32, a, None) == B.ERR_NULL
+    assert L.dirotq_linear_static(a, a + 8, a, None, 4, 8, 64, 0, 32, a, None) == B.ERR_ALIGN
+    assert L.dirotq_linear_static(a, a, a, None, 0, 8, 64, 0, 32, a, None) == B.OK
+    # beyond the fixed size: refused before any device is touched
+    assert B.workspace_bytes(16384, 12288, 128, 64) > B.STATIC_SCRATCH_BYTES
+    assert L.dirotq_linear_static(a, a, a, None, 16384, 8, 12288, 128, 64, a, None) == B.ERR_STATIC_LIMIT
+    assert b"64 MiB" in L.dirotq_strerror(B.ERR_STATIC_LIMIT)
     # shared-input entry point: host arrays of device pointers
     vp2 = (ctypes.c_void_p * 2)(a, a)
     ns2 = (ctypes.c_int * 2)(8, 16)
