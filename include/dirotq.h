@@ -21,6 +21,20 @@
  * amax = max|v|; s = fp16_rne(min(amax / 7, 65504)); s == 0 -> all codes 0; else
  * inv = 1 / float(s), code = clip(rint(v * inv), -7, 7).
  *
+ * Where this header departs from the plainest reading of the paper's problem statement
+ * (all of it layout, none of it arithmetic):
+ *  - the online rotation operand is Qt = bf16(Q^T), one basis direction per row, made
+ *    once per layer by dirotq_prepare_rotation (both GEMM operands then stream
+ *    K-contiguous rows); Q itself is only an argument of the offline calls;
+ *  - activation scales (and zero-points) are group-major, [G][M], not [M][G];
+ *  - an activation nibble is sign-magnitude (bit 3 sign, bits 0-2 |q|), not two's
+ *    complement: that form expands to the fp8 operand of the matrix pipe in two
+ *    bit operations; the weight blob is private (dirotq_export_weights gives the
+ *    canonical int8 codes back);
+ *  - K and r must be multiples of 32 (one 16-byte chunk of packed codes);
+ *  - dirotq_linear takes its intermediates in a caller-supplied workspace
+ *    (dirotq_linear_static keeps them in the library's own fixed array instead).
+ *
  * General conventions
  *  - Every pointer is a DEVICE pointer unless marked "host".  The caller owns all
  *    memory; the library never allocates or frees device memory.
@@ -88,20 +102,23 @@ int dirotq_workspace_bytes(int M, int K, int r, int g, size_t* bytes /*host out*
 int dirotq_prepare_rotation(const float* Q, int K, uint16_t* Qt_bf16 /*out*/, void* stream);
 
 /*
- * Offline weight fusion ("absorbed into the weights offline", Section 4.2):
+ * Offline weight fusion (the step of Section 4.2 that folds the transposed rotation into
+ * the weights, just before the forward-computation equation):
  * W' = W Q with fp64 accumulation rounded to fp32; W'_h = bf16_rne(W'[:, 0:r]);
  * W'[:, r:K] quantized per output channel and per group of g with the quantizer
  * above (round-to-nearest stands in for GPTQ).  W fp32 [N,K], Q fp32 [K,K] as in
  * dirotq_prepare_rotation.  `blob` receives dirotq_weights_bytes bytes in a layout
  * private to this library (read it back with dirotq_export_weights).  `scratch`:
- * dirotq_prepare_scratch_bytes bytes, contents undefined afterwards.
+ * dirotq_prepare_scratch_bytes bytes, contents undefined afterwards.  Shapes with more than
+ * 2^31 - 1 tiles of 64 x 64 in W (N K > 2^43) return DIROTQ_ERR_SHAPE.
  */
 int dirotq_prepare_weights(const float* W, const float* Q, int N, int K, int r, int g,
                            void* blob /*out*/, void* scratch, size_t scratch_bytes, void* stream);
 
 /*
  * Build a blob from already-quantized weights: Wh bf16 [N,r], codes int8 [N,K-r]
- * with values in [-7,7], sw fp16 [N,G] (channel-major).  Wh may be NULL when r == 0,
+ * with values in [-7,7] (anything outside is clamped to that range: -8 is not a code of
+ * the symmetric quantizer), sw fp16 [N,G] (channel-major).  Wh may be NULL when r == 0,
  * codes and sw may be NULL when r == K.
  */
 int dirotq_import_weights(const uint16_t* Wh_bf16, const int8_t* codes, const uint16_t* sw_fp16,

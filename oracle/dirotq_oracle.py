@@ -194,8 +194,8 @@ def dequantize_groups_asym(codes, scales, zeros, g: int) -> np.ndarray:
 
 # --------------------------------------------------------------------------
 # offline: fuse the rotation into the weights, split, quantize
-# ("the transpose of the combined rotation can be absorbed into the weights
-#  offline"; RTN stands in for GPTQ on the residual weights)
+# (weight-fusion step of Section 4.2, just before the forward-computation
+#  equation; RTN stands in for GPTQ on the residual weights)
 # --------------------------------------------------------------------------
 def prepare_weights(W: np.ndarray, Q32: np.ndarray, r: int, g: int):
     """W float32 [N,K], Q32 float32 [K,K] -> (Wh float32 bf16-valued [N,r],

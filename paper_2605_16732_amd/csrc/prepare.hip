@@ -1,5 +1,5 @@
-// Offline side of the layer (Section 4.2 of the paper: the transpose rotation is
-// absorbed into the weights offline): W' = W Q in fp64, split at r, round-to-nearest
+// Offline side of the layer (weight-fusion step of Section 4.2 of the paper, just before
+// its forward-computation equation): W' = W Q in fp64, split at r, round-to-nearest
 // INT4 with fp16 group scales; plus import/export of the prepared-weight blob and the
 // bf16 transposed rotation operand.  None of this is on the per-step hot path.
 #include "dirotq_internal.h"
@@ -31,7 +31,9 @@ __global__ __launch_bounds__(256) void fuse_rotation_fp64_kernel(const float* __
   __shared__ double Ws[16][64 + 2];
   __shared__ double Qs[16][64 + 2];
   const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
-  const int n0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  // one workgroup per 64 x 64 tile, tiles numbered row-major over (n tile, c tile) on a 1-D grid
+  const int n_ct = (K + 63) / 64;
+  const int n0 = (int)(blockIdx.x / n_ct) * 64, c0 = (int)(blockIdx.x % n_ct) * 64;
   double acc[4][4];
 #pragma unroll
   for (int i = 0; i < 4; i++)
@@ -119,10 +121,15 @@ int launch_prepare_weights(const float* W, const float* Q, int N, int K, int r, 
                            float* scratch, hipStream_t s) {
   const BlobLayout L = blob_layout(N, K, r, g);
   char* bp = (char*)blob;
-  hipLaunchKernelGGL(fuse_rotation_fp64_kernel, dim3((K + 63) / 64, (N + 63) / 64), dim3(256), 0, s, W, Q, N,
-                     K, scratch);
-  const long units = (long)N * (r / 32) + (long)N * ((K - r) / g);
-  hipLaunchKernelGGL(split_quantize_rows_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, s,
+  // 1-D grids: both launches must stay within 2^31 - 1 workgroups (only shapes whose fp32 scratch alone
+  // would exceed 2^44 bytes get there)
+  const long n_tiles = (long)((K + 63) / 64) * (long)((N + 63) / 64);
+  const long n_units = (long)N * (r / 32) + (long)N * ((K - r) / g);
+  if (n_tiles > 0x7FFFFFFFL || (n_units + 255) / 256 > 0x7FFFFFFFL) return DIROTQ_ERR_SHAPE;
+  hipLaunchKernelGGL(fuse_rotation_fp64_kernel, dim3((unsigned)n_tiles), dim3(256), 0, s, W, Q, N, K, scratch);
+  hipError_t e0 = hipGetLastError();
+  if (e0 != hipSuccess) return hip_failed(e0);      // nothing else is enqueued on an unwritten scratch
+  hipLaunchKernelGGL(split_quantize_rows_kernel, dim3((unsigned)((n_units + 255) / 256)), dim3(256), 0, s,
                      scratch, N, K, r, g, (uint16_t*)(bp + L.off_wh), (uint8_t*)(bp + L.off_codes),
                      (uint16_t*)(bp + L.off_sw), (int16_t*)(bp + L.off_wsum));
   hipError_t e = hipGetLastError();
@@ -140,13 +147,15 @@ __global__ __launch_bounds__(256) void import_kernel(const uint16_t* __restrict_
   const long n_wh = (long)N * r, n_q = (long)N * (K - r) / 2;
   const int G = (K - r) / g;
   if (i < n_wh) bwh[i] = Wh[i];
-  if (i < n_q) bq[i] = (uint8_t)(code_nibble(codes[2 * i]) | (code_nibble(codes[2 * i + 1]) << 4));
+  // (codes outside [-7, 7] are clamped: the symmetric 4-bit quantizer never produces -8)
+  auto clamp7 = [](int q) { return min(max(q, -7), 7); };
+  if (i < n_q) bq[i] = (uint8_t)(code_nibble(clamp7(codes[2 * i])) | (code_nibble(clamp7(codes[2 * i + 1])) << 4));
   if (i < (long)N * G) {
     const int n = (int)(i / G), j = (int)(i % G);
     bsw[(size_t)j * N + n] = sw[i];
     const int8_t* c = codes + (size_t)n * (K - r) + (size_t)j * g;
     int sum = 0;
-    for (int p = 0; p < g; p++) sum += c[p];
+    for (int p = 0; p < g; p++) sum += clamp7(c[p]);
     bwsum[(size_t)j * N + n] = (int16_t)sum;
   }
 }

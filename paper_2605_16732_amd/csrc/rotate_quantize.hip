@@ -597,9 +597,6 @@ int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, 
   const long n_tc256 = (Kv + 255) / 256;
   const long big_tiles = n_tc256 * ((M + 255) / 256);    // 256 channels x 256 tokens
   const long mid_tiles = n_tc256 * ((M + 127) / 128);    // 256 channels x 128 tokens
-#ifdef DIROTQ_RQ_FORCE   // build-time tuning aid: -DDIROTQ_RQ_FORCE=WGC,WGT,BK,MI (K % BK must be 0)
-  return launch_cfg<DIROTQ_RQ_FORCE>(o, x, Qt, M, K, r, g, s);
-#endif
   if (K % 64 != 0) {
     if (mid_tiles >= 100) return launch_cfg<2, 2, 32, 32>(o, x, Qt, M, K, r, g, s);
     return launch_cfg<1, 2, 32, 32>(o, x, Qt, M, K, r, g, s);
