@@ -197,10 +197,14 @@ def dequantize_groups_asym(codes, scales, zeros, g: int) -> np.ndarray:
 # (weight-fusion step of Section 4.2, just before the forward-computation
 #  equation; RTN stands in for GPTQ on the residual weights)
 # --------------------------------------------------------------------------
-def prepare_weights(W: np.ndarray, Q32: np.ndarray, r: int, g: int):
-    """W float32 [N,K], Q32 float32 [K,K] -> (Wh float32 bf16-valued [N,r],
-    qw int8 [N,K-r], sw float16 [N,G]).  W' = W Q in float64, rounded to fp32."""
-    Wp = (np.asarray(W, np.float64) @ np.asarray(Q32, np.float64)).astype(np.float32)
+def fuse_weights(W: np.ndarray, Q32: np.ndarray) -> np.ndarray:
+    """W' = W Q: W float32 [N,K], Q32 float32 [K,K]; float64 accumulation, one rounding to fp32."""
+    return (np.asarray(W, np.float64) @ np.asarray(Q32, np.float64)).astype(np.float32)
+
+
+def split_quantize_weights(Wp: np.ndarray, r: int, g: int):
+    """Fused weights W' fp32 [N,K] -> (Wh float32 bf16-valued [N,r], qw int8 [N,K-r], sw float16 [N,G]):
+    the first r input channels in 16 bits, the rest per output channel and group with the quantizer."""
     Wh = round_to_bf16(Wp[:, :r])
     if r < Wp.shape[1]:
         qw, sw = quantize_groups(Wp[:, r:], g)
@@ -208,6 +212,12 @@ def prepare_weights(W: np.ndarray, Q32: np.ndarray, r: int, g: int):
         qw = np.zeros((Wp.shape[0], 0), np.int8)
         sw = np.zeros((Wp.shape[0], 0), np.float16)
     return Wh, qw, sw
+
+
+def prepare_weights(W: np.ndarray, Q32: np.ndarray, r: int, g: int):
+    """W float32 [N,K], Q32 float32 [K,K] -> (Wh float32 bf16-valued [N,r],
+    qw int8 [N,K-r], sw float16 [N,G]).  W' = W Q in float64, rounded to fp32."""
+    return split_quantize_weights(fuse_weights(W, Q32), r, g)
 
 
 # --------------------------------------------------------------------------

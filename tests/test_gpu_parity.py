@@ -9,8 +9,9 @@ from oracle import dirotq_oracle as O
 from paper_2605_16732_amd import binding as B
 from paper_2605_16732_amd import inputs as I
 
-from gpu_util import (pack_codes, unpack_codes, check_codes_statistical, check_output, dev, dev_bf16, gpu_rotate_quantize, host_bf16_bits,
-                      host_f16, import_blob, layer_with_oracle)
+from gpu_util import (pack_codes, unpack_codes, check_codes_statistical, check_output, check_xh, dev, dev_bf16,
+                      gpu_rotate_quantize, host_bf16_bits, host_f16, import_blob, layer_with_oracle, oracle_rotation,
+                      oracle_fused_weights)
 
 pytestmark = pytest.mark.gpu
 
@@ -195,45 +196,62 @@ def test_w4a4_gemm_matches_oracle_on_identical_inputs(M, N, K, r, g, use_bias):
 
 
 # ------------------------------------------------------------------ end to end
-def _end_to_end(shape, M=None, rows=None, residual_rotation=False):
-    L, (Wh, qw, sw), ref = layer_with_oracle(shape, M=M, rows=rows, residual_rotation=residual_rotation)
+def _end_to_end(shape, M=None, y_rows=None, residual_rotation=False, same_rows=None, blob_from="import", base=None):
+    """Rotation + quantization of EVERY token against the oracle (codes, scales, bf16 part), then the
+    fused layer's output against the oracle's on `y_rows` (default: every token).  `same_rows` (default:
+    y_rows) are the tokens on which the GEMM is also checked on identical inputs.  `base` names the layer
+    whose draws are used (shapes that differ only in r and g share them)."""
+    draws = shape if base is None else base
+    L, x, Q, xhat = oracle_rotation(draws, M, residual_rotation)
+    Wp = oracle_fused_weights(draws, M, residual_rotation)
     Mx, K, N, r, g = L.x_bits.shape[0], shape.K, shape.N, shape.r, shape.g
+    Wh, qw, sw = O.split_quantize_weights(Wp, r, g)
+    xh_r, qx_r, sx_r = O.split_quantize(xhat, r, g)
     Qt = B.prepare_rotation(dev(L.Q32))
     np.testing.assert_array_equal(host_bf16_bits(Qt), np.ascontiguousarray(L.Q_bits.T))
-    blob = import_blob(Wh, qw, sw, N, K, r, g)
-    # stage 1: rotation + quantization against the oracle's
+    if blob_from == "import":
+        blob = import_blob(Wh, qw, sw, N, K, r, g)
+    else:                                        # the library's own offline fusion (fp64 on both sides)
+        blob = B.prepare_weights(dev(L.W), dev(L.Q32), r, g)
+    # stage 1: rotation + quantization of every token against the oracle's
     (xh_d, xl_d, sx_d), (xh_g, qx_g, sx_g) = gpu_rotate_quantize(L.x_bits, Qt, r, g)
-    sel = slice(None) if rows is None else np.asarray(rows)
-    stats = check_codes_statistical(ref["xhat"][:, r:], qx_g[sel], sx_g[sel], ref["qx"], ref["sx"], g)
-    if r:
-        # bf16 part: the GPU sums in fp32 (error <~ sqrt(K) 2^-24 |x_m| |Q_c|, bounded here by
-        # 1e-5 |x_m|), then both sides round to bf16 (one ulp = 2^-7 relative at most); nearly
-        # all elements are bit-identical
-        xn = np.linalg.norm(I.bf16_bits_to_f32(L.x_bits)[sel].astype(np.float64), axis=1)[:, None]
-        err = np.abs(xh_g[sel].astype(np.float64) - ref["xh"])
-        assert np.all(err <= 2.0 ** -7 * np.abs(ref["xh"]) + 1e-5 * xn)
-        assert (err != 0).mean() <= 2e-2
+    stats = dict(agree=1.0, code_flips=0, scale_flips=0, groups=0, worst_flip_slack=0.0)
+    if r < K:
+        stats = check_codes_statistical(xhat[:, r:], qx_g, sx_g, qx_r, sx_r, g, x=x, Q=Q, col0=r)
+    xh_frac = check_xh(xh_g, xh_r, x, K) if r else 0.0
     # stage 2: GEMM on the GPU's own intermediates against the oracle's combine of the same
-    y32_same, _ = O.combine(xh_g[sel], qx_g[sel], sx_g[sel], Wh, qw, sw, g)
+    sel = slice(None) if y_rows is None else np.asarray(y_rows)
+    ssel = sel if same_rows is None else np.asarray(same_rows)
     yf = B.w4a4_gemm(xh_d if r else None, xl_d, sx_d, blob, Mx, N, K, r, g, out_dtype=torch.float32)
     torch.cuda.synchronize()
-    assert np.abs(yf.cpu().numpy()[sel] - y32_same).max() <= 1e-5 * np.abs(y32_same).max()
+    if blob_from == "import":
+        y32_same, _ = O.combine(xh_g[ssel], qx_g[ssel], sx_g[ssel], Wh, qw, sw, g)
+        assert np.abs(yf.cpu().numpy()[ssel] - y32_same).max() <= 1e-5 * np.abs(y32_same).max()
+    del yf
     # the fused entry point, bf16 out, against the oracle end to end
+    y32, _ = O.combine(xh_r[sel], qx_r[sel], sx_r[sel], Wh, qw, sw, g)
     y = B.linear(dev_bf16(L.x_bits), Qt, blob, N, r, g)
     torch.cuda.synchronize()
     yg = O.from_bf16_bits(host_bf16_bits(y))
-    row_err, max_err = check_output(yg[sel], ref["y32"], tol=1e-2)
+    row_err, max_err = check_output(yg[sel], y32, tol=1e-2)
     # and it is exactly the two-step path
     y2 = B.w4a4_gemm(xh_d if r else None, xl_d, sx_d, blob, Mx, N, K, r, g, out_dtype=torch.bfloat16)
     torch.cuda.synchronize()
     assert torch.equal(y, y2)
-    _say(f"{shape.name}: codes agree {stats['agree']:.6f}, code flips {stats['code_flips']}, scale flips "
-         f"{stats['scale_flips']}/{stats['groups']}, out row-rel {row_err:.2e} max-rel {max_err:.2e}")
+    n_y = Mx if y_rows is None else len(y_rows)
+    _say(f"{shape.name}: {Mx} tokens, codes agree {stats['agree']:.6f}, code flips {stats['code_flips']}, scale flips "
+         f"{stats['scale_flips']}/{stats['groups']} (worst {stats['worst_flip_slack']:.2f} of the allowed distance), "
+         f"bf16 part differs on {xh_frac:.4f}, out ({n_y} tokens) row-rel {row_err:.2e} max-rel {max_err:.2e}")
     return stats
 
 
 def test_end_to_end_small_config():
     _end_to_end(I.SMALL)
+
+
+def test_end_to_end_small_config_with_library_prepared_weights():
+    # configs[0] with the blob from dirotq_prepare_weights (W Q in fp64 on the GPU) instead of the oracle's
+    _end_to_end(I.SMALL, blob_from="prepare")
 
 
 def test_end_to_end_ragged_tokens_and_outputs():
@@ -244,32 +262,47 @@ def test_end_to_end_ragged_tokens_and_outputs():
     _end_to_end(shp)
 
 
-def test_end_to_end_pixart_fc1_sampled_rows():
-    # full PixArt fc1 launch; the oracle is evaluated on 96 sampled tokens
-    shp = I.PIXART[2]
-    rows = np.random.default_rng(0).choice(shp.M, size=96, replace=False)
-    rows.sort()
-    _end_to_end(shp, rows=rows)
+def _every(M, step):
+    return np.arange(0, M, step)
 
 
-def test_end_to_end_flux_fc1_full_launch_sampled_rows():
-    # the launch configuration bench.py times (M=4608, K=3072, N=12288, r=128, g=64); the
-    # oracle is evaluated on 64 sampled tokens (tokens are independent rows of the layer)
-    shp = I.FLUX[2]
-    rows = np.sort(np.random.default_rng(1).choice(shp.M, size=64, replace=False))
-    _end_to_end(shp, rows=rows)
+@pytest.mark.parametrize("idx", range(4))
+def test_end_to_end_pixart_layers_every_token(idx):
+    # the four PixArt-shaped layers at full size (M = 4096): every token through rotation, quantization and
+    # the fused layer; the identical-input GEMM check on every 8th token
+    shp = I.PIXART[idx]
+    _end_to_end(shp, same_rows=_every(shp.M, 8))
 
 
-def test_end_to_end_flux_fc2_full_launch_sampled_rows():
-    # K=12288 (190 groups): the rotation-bound layer of the benchmark
-    shp = I.FLUX[3]
-    rows = np.sort(np.random.default_rng(2).choice(shp.M, size=32, replace=False))
-    _end_to_end(shp, rows=rows)
+@pytest.mark.parametrize("idx", range(4))
+def test_end_to_end_flux_layers_every_token(idx):
+    # the launch configurations bench.py times (M = 4608; QKV, out-projection, fc1 with K = 3072, fc2 with
+    # K = 12288: two rotation launches, 190 groups): every token against the oracle
+    shp = I.FLUX[idx]
+    _end_to_end(shp, same_rows=_every(shp.M, 8))
+
+
+@pytest.mark.parametrize("M", [1024, 16384, 32768])
+def test_end_to_end_token_sweep(M):
+    # the token sweep on the PixArt fc1 shape; 16384 and 32768 tokens take the two-launch rotation (full rounds
+    # of 256 x 256 tiles, then half-size tiles) with the short-K threshold.  Every token is quantized and
+    # compared; the output is compared on every 4th token.
+    shp = [s for s in I.TOKEN_SWEEP if s.M == M][0]
+    _end_to_end(shp, y_rows=_every(M, 4) if M > 4096 else None, same_rows=_every(M, 16))
+
+
+@pytest.mark.parametrize("r,g", [(s.r, s.g) for s in I.ABLATION])
+def test_end_to_end_rank_group_ablation_full_shape(r, g):
+    # the 12 (r, g) pairs of the rank/group ablation at the full fc2 shape (M = 4608, K = 12288, N = 3072), on
+    # the draws of the FLUX fc2 layer (as bench.py does): one oracle rotation and one fused weight matrix serve
+    # all pairs.  Codes, scales and the bf16 part of every token; the output on every 8th token.
+    shp = [s for s in I.ABLATION if (s.r, s.g) == (r, g)][0]
+    _end_to_end(shp, y_rows=_every(shp.M, 8), same_rows=_every(shp.M, 32), base=I.FLUX[3])
 
 
 @pytest.mark.parametrize("r,g", [(0, 32), (32, 32), (0, 128), (256, 128), (256, 64)])
 def test_end_to_end_rank_group_grid(r, g):
-    # the (r, g) pairs of the rank/group ablation, on a reduced fc2-like shape with a ragged M
+    # (r, g) pairs on a reduced fc2-like shape with a ragged M
     shp = I.LayerShape(f"abl_r{r}_g{g}", 200, 1536, 384, r, g, 8, 8, r * 4 + g)
     _end_to_end(shp)
 

@@ -78,3 +78,37 @@ def test_seeded_and_prefix_stable():
     np.testing.assert_array_equal(a[:4], b)
     c = I.make_activations(I.SMALL, 4, seed=1)
     assert not np.array_equal(b, c)
+
+
+def _max_orthogonality_defect(Q32: np.ndarray, block: int = 2048) -> float:
+    """max |Q^T Q - I| with the fp32 matrix evaluated in fp64, upper triangle by blocks of columns."""
+    K = Q32.shape[0]
+    worst = 0.0
+    for i0 in range(0, K, block):
+        Qi = Q32[:, i0:i0 + block].astype(np.float64)
+        for j0 in range(i0, K, block):
+            Qj = Qi if j0 == i0 else Q32[:, j0:j0 + block].astype(np.float64)
+            Gm = Qi.T @ Qj
+            if j0 == i0:
+                Gm -= np.eye(Gm.shape[0])
+            worst = max(worst, float(np.abs(Gm).max()))
+    return worst
+
+
+@pytest.mark.parametrize("idx", [2, 3])
+def test_benchmark_bases_are_orthogonal(idx):
+    """The fp32 bases the benchmark and the full-size parity tests use -- K = 3072 (eigendecomposition of the
+    second moment) and K = 12288 (2048 calibration rows: Gram-matrix eigenvectors completed by a full QR) --
+    satisfy max |Q^T Q - I| < 1e-5 in fp64, as the small config's does."""
+    shp = I.FLUX[idx]
+    s = I.channel_scales(shp)
+    Zc = np.random.default_rng([0, shp.config_id, shp.layer_id, 2]).standard_normal((I.N_CALIB, shp.K), dtype=np.float32)
+    Q, lam = I.pca_basis(Zc * s[None, :])
+    Q32 = np.ascontiguousarray(Q, dtype=np.float32)
+    del Q, Zc
+    assert Q32.shape == (shp.K, shp.K)
+    assert _max_orthogonality_defect(Q32) < 1e-5
+    assert np.all(np.diff(lam) <= 1e-9 * lam[0])
+    # the same draws as make_layer: spot-check against it on the smaller basis
+    if shp.K <= 4096:
+        np.testing.assert_array_equal(I.make_layer(shp).Q32, Q32)

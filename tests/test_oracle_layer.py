@@ -437,3 +437,11 @@ def test_w4a16_agrees_with_the_w4a4_combine_on_code_times_scale_activations():
     y_a, _ = O.linear_w4a16(x, qw, sw, g)
     y_b, _ = O.combine(np.zeros((M, 0), np.float32), qx, sx, np.zeros((N, 0), np.float32), qw, sw, g)
     np.testing.assert_array_equal(y_a, y_b)
+
+
+def test_qsnr_hand_value():
+    """QSNR = 10 log10(|ref|^2 / |ref - approx|^2): ref (3, 4), approx (3, 3.5) -> 25 / 0.25 = 100 -> 20 dB.
+    (20 log10 would give 40; swapped arguments 10 log10(21.25 / 0.25) = 19.29.)"""
+    assert abs(O.qsnr_db(np.array([3.0, 4.0]), np.array([3.0, 3.5])) - 20.0) < 1e-12
+    assert abs(O.qsnr_db(np.array([3.0, 3.5]), np.array([3.0, 4.0])) - 10.0 * np.log10(85.0)) < 1e-12
+    assert O.qsnr_db(np.array([1.0, -2.0]), np.array([1.0, -2.0])) > 200.0          # exact: capped, not infinite
