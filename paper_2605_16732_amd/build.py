@@ -10,6 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdirotq.so")
+PROBE_LIB = os.path.join(HERE, "libdirotq_probe.so")     # matrix-pipe rate probes used by bench.py only
 SOURCES = ["dirotq_abi.hip", "rotate_quantize.hip", "w4a4_gemm.hip", "w4a8_gemm.hip", "w4a16_gemm.hip", "prepare.hip"]
 
 # packed-fp32 VALU instructions are switched off on purpose (they have produced wrong
@@ -58,6 +59,10 @@ def build(verbose: bool = True, extra_flags: list[str] | None = None) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
+    cmd = [cc, *flags, "-shared", os.path.join(CSRC, "bench_probe.hip"), "-o", PROBE_LIB]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)
     return LIB
 
 
