@@ -104,6 +104,9 @@ int launch_w4a16_gemm(const uint16_t* x, const void* blob, const uint16_t* bias,
 int launch_w4a4_gemm(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const uint16_t* zx,
                      const void* blob, const uint16_t* bias, int M, int N, int K, int r, int g, void* y,
                      int y_dtype, hipStream_t s);
+// symmetric activation codes only; 4-bit part not empty (wave-specialised schedule of the same arithmetic)
+int launch_w4a4_gemm_ws(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const void* blob,
+                        const uint16_t* bias, int M, int N, int K, int r, int g, void* y, int y_dtype, hipStream_t s);
 int launch_prepare_rotation(const float* Q, int K, uint16_t* Qt, hipStream_t s);
 int launch_prepare_weights(const float* W, const float* Q, int N, int K, int r, int g, void* blob,
                            float* scratch, hipStream_t s);
@@ -120,6 +123,13 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
   uint32_t u = __builtin_bit_cast(uint32_t, f);
   u += 0x7FFFu + ((u >> 16) & 1u);
   return (uint16_t)(u >> 16);
+}
+// two floats -> two bf16 in one dword (lo | hi << 16), round to nearest even: the packed hardware conversion
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2_bits(float lo, float hi) {
+  typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) {
   return __builtin_bit_cast(float, (uint32_t)b << 16);

@@ -20,6 +20,109 @@ __device__ __forceinline__ int tile_off_bytes(int row, int chunk) {
   return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
 }
 
+// Bias and store of a wave's 64 n x 64 token block (2 x 2 accumulators of 32 x 32 in the D[n][token]
+// orientation: a lane owns one token and 4 consecutive output channels per register quad -> 8-byte bf16
+// stores).  n_base / m_base: first output channel / token of the block.
+template <bool OUT_F32>
+__device__ __forceinline__ void store_tile(const f32x16 (&acc)[2][2], const uint16_t* __restrict__ bias,
+                                           void* __restrict__ y, int M, int N, int m_base, int n_base) {
+  int l = threadIdx.x & 63;
+  asm volatile("" : "+v"(l));   // (a caller that loops over tiles forms these addresses per tile, not once in registers)
+  const int h = l >> 5;
+  const bool vec_ok = (N % 4) == 0;
+  if (vec_ok && n_base + 64 <= N) {
+    // The block's 64 output channels all exist and rows are 8-byte aligned: straight-line code, one row
+    // pointer per token, the channel offsets as immediates.
+    float bv[2][4][4];
+    if (bias) {
+#pragma unroll
+      for (int i = 0; i < 2; i++)
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+          const uint2 bb = *(const uint2*)(bias + n_base + i * 32 + 8 * q + 4 * h);
+          bv[i][q][0] = bf16_bits_to_f32((uint16_t)(bb.x & 0xFFFF));
+          bv[i][q][1] = bf16_bits_to_f32((uint16_t)(bb.x >> 16));
+          bv[i][q][2] = bf16_bits_to_f32((uint16_t)(bb.y & 0xFFFF));
+          bv[i][q][3] = bf16_bits_to_f32((uint16_t)(bb.y >> 16));
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 2; j++) {
+      const int m = m_base + j * 32 + (l & 31);
+      if (m >= M) continue;
+      const size_t row = (size_t)m * N + n_base + 4 * h;
+#pragma unroll
+      for (int i = 0; i < 2; i++)
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+          float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+          if (bias) {
+#pragma unroll
+            for (int e = 0; e < 4; e++) v[e] += bv[i][q][e];
+          }
+          if (OUT_F32) {
+            *(float4*)((float*)y + row + i * 32 + 8 * q) = make_float4(v[0], v[1], v[2], v[3]);
+          } else {
+            uint2 o;
+            o.x = f32x2_to_bf16x2_bits(v[0], v[1]);
+            o.y = f32x2_to_bf16x2_bits(v[2], v[3]);
+            *(uint2*)((uint16_t*)y + row + i * 32 + 8 * q) = o;
+          }
+        }
+    }
+    return;
+  }
+#pragma unroll
+  for (int j = 0; j < 2; j++) {
+    const int m = m_base + j * 32 + (l & 31);
+    if (m >= M) continue;
+#pragma unroll
+    for (int i = 0; i < 2; i++)
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        const int n = n_base + i * 32 + 8 * q + 4 * h;
+        if (n >= N) continue;
+        float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+        const bool full = vec_ok && n + 4 <= N;
+        if (bias) {
+          if (full) {
+            const uint2 bb = *(const uint2*)(bias + n);
+            v[0] += bf16_bits_to_f32((uint16_t)(bb.x & 0xFFFF));
+            v[1] += bf16_bits_to_f32((uint16_t)(bb.x >> 16));
+            v[2] += bf16_bits_to_f32((uint16_t)(bb.y & 0xFFFF));
+            v[3] += bf16_bits_to_f32((uint16_t)(bb.y >> 16));
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; e++)
+              if (n + e < N) v[e] += bf16_bits_to_f32(bias[n + e]);
+          }
+        }
+        if (OUT_F32) {
+          float* dst = (float*)y + (size_t)m * N + n;
+          if (full) {
+            *(float4*)dst = make_float4(v[0], v[1], v[2], v[3]);
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; e++)
+              if (n + e < N) dst[e] = v[e];
+          }
+        } else {
+          uint16_t* dst = (uint16_t*)y + (size_t)m * N + n;
+          if (full) {
+            uint2 o;
+            o.x = f32x2_to_bf16x2_bits(v[0], v[1]);
+            o.y = f32x2_to_bf16x2_bits(v[2], v[3]);
+            *(uint2*)dst = o;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; e++)
+              if (n + e < N) dst[e] = f32_to_bf16_bits(v[e]);
+          }
+        }
+      }
+  }
+}
+
 // smem: at least 32 KB, free for reuse (the caller's main loop is over; a barrier is taken
 // here before the first store).  rowA / rowB: this lane's operand rows of the two n tiles
 // and the two token tiles within a [256 rows] stage (weights 0..127, tokens 128..255).
@@ -76,57 +179,7 @@ __device__ __forceinline__ void gemm_tail(f32x16 (&acc)[2][2], unsigned char* sm
     }
   }
 
-  // ---- epilogue: 4 consecutive output channels per register quad ------------------
-  const bool vec_ok = (N % 4) == 0;
-#pragma unroll
-  for (int j = 0; j < 2; j++) {
-    const int m = m0 + wt * 64 + j * 32 + (l & 31);
-    if (m >= M) continue;
-#pragma unroll
-    for (int i = 0; i < 2; i++)
-#pragma unroll
-      for (int q = 0; q < 4; q++) {
-        const int n = n0 + wn * 64 + i * 32 + 8 * q + 4 * h;
-        if (n >= N) continue;
-        float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-        const bool full = vec_ok && n + 4 <= N;
-        if (bias) {
-          if (full) {
-            const uint2 bb = *(const uint2*)(bias + n);
-            v[0] += bf16_bits_to_f32((uint16_t)(bb.x & 0xFFFF));
-            v[1] += bf16_bits_to_f32((uint16_t)(bb.x >> 16));
-            v[2] += bf16_bits_to_f32((uint16_t)(bb.y & 0xFFFF));
-            v[3] += bf16_bits_to_f32((uint16_t)(bb.y >> 16));
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; e++)
-              if (n + e < N) v[e] += bf16_bits_to_f32(bias[n + e]);
-          }
-        }
-        if (OUT_F32) {
-          float* dst = (float*)y + (size_t)m * N + n;
-          if (full) {
-            *(float4*)dst = make_float4(v[0], v[1], v[2], v[3]);
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; e++)
-              if (n + e < N) dst[e] = v[e];
-          }
-        } else {
-          uint16_t* dst = (uint16_t*)y + (size_t)m * N + n;
-          if (full) {
-            uint2 o;
-            o.x = f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16);
-            o.y = f32_to_bf16_bits(v[2]) | ((uint32_t)f32_to_bf16_bits(v[3]) << 16);
-            *(uint2*)dst = o;
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; e++)
-              if (n + e < N) dst[e] = f32_to_bf16_bits(v[e]);
-          }
-        }
-      }
-  }
+  store_tile<OUT_F32>(acc, bias, y, M, N, m0 + wt * 64, n0 + wn * 64);
 }
 
 }  // namespace dirotq

@@ -36,6 +36,9 @@
 // tile s, and the LDS operand reads of the next group are issued one sweep ahead.
 #include <atomic>
 
+#include <cstdlib>
+#include <cstring>
+
 #include "gemm_tail.h"
 
 namespace dirotq {
@@ -432,6 +435,21 @@ static int launch_one(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx,
   return e == hipSuccess ? DIROTQ_OK : hip_failed(e);
 }
 
+// Which of the two schedules runs a symmetric layer.  The wave-specialised kernel (persistent workgroups, one per
+// CU, 256 x 128 tiles) is the faster one per tile; the kernel in this file (128 x 128 tiles, two workgroups per
+// CU) spreads a small problem over more CUs.  Measured crossover: about 128 of the larger tiles.
+// DIROTQ_W4A4_KERNEL=ws / tile in the environment forces one of them wherever it applies (the tests use it to run
+// both on the same inputs).
+static bool w4a4_ws_preferred(int M, int N, int K, int r) {
+  if (K - r <= 0) return false;
+  if (const char* f = getenv("DIROTQ_W4A4_KERNEL")) {
+    if (!strcmp(f, "ws")) return true;
+    if (!strcmp(f, "tile")) return false;
+  }
+  const long tiles = (long)((M + 127) / 128) * ((N + 255) / 256);
+  return tiles >= 128;
+}
+
 int launch_w4a4_gemm(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const uint16_t* zx,
                      const void* blob, const uint16_t* bias, int M, int N, int K, int r, int g, void* y,
                      int y_dtype, hipStream_t s) {
@@ -442,6 +460,8 @@ int launch_w4a4_gemm(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, 
                      : launch_one<GS, false, true>(xh, xl, sx, zx, blob, bias, M, N, K, r, y, s);     \
     return y_dtype ? launch_one<GS, true, false>(xh, xl, sx, zx, blob, bias, M, N, K, r, y, s)        \
                    : launch_one<GS, false, false>(xh, xl, sx, zx, blob, bias, M, N, K, r, y, s);
+  if (!zx && w4a4_ws_preferred(M, N, K, r))
+    return launch_w4a4_gemm_ws(xh, xl, sx, blob, bias, M, N, K, r, g, y, y_dtype, s);
   switch (g) {
     DIROTQ_CASE(32)
     DIROTQ_CASE(64)

@@ -123,8 +123,18 @@ def test_rotate_quantize_ties_and_clip():
 
 
 # ------------------------------------------------------------------ kernel B, exact
-@pytest.mark.parametrize("M,N,K,g", [(130, 200, 256, 32), (257, 136, 448, 64), (64, 129, 384, 128), (5, 8, 64, 32)])
-def test_w4a4_integer_dot_is_exact(M, N, K, g):
+@pytest.fixture(params=["tile", "ws"])
+def schedule(request, monkeypatch):
+    """Kernel B has two schedules of the same arithmetic (128 x 128 tiles, two workgroups per CU; persistent
+    wave-specialised workgroups on 256 x 128 tiles); the library picks by problem size.  The environment switch
+    read at every launch forces one, so that both run on the same inputs."""
+    monkeypatch.setenv("DIROTQ_W4A4_KERNEL", request.param)
+    return request.param
+
+
+@pytest.mark.parametrize("M,N,K,g", [(130, 200, 256, 32), (257, 136, 448, 64), (64, 129, 384, 128), (5, 8, 64, 32),
+                                     (140, 520, 96, 32)])
+def test_w4a4_integer_dot_is_exact(M, N, K, g, schedule):
     """Unit scales, no 16-bit branch: the fp32 output is the plain integer dot product
     (< 2^24), so it must be exact -- the int32 group accumulators are bit-exact."""
     _say(f"w4a4 integer M={M} N={N} K={K} g={g}")
@@ -144,7 +154,7 @@ def test_w4a4_integer_dot_is_exact(M, N, K, g):
     assert want[0, 0] == -49 * K
 
 
-def test_w4a4_power_of_two_scales_exact():
+def test_w4a4_power_of_two_scales_exact(schedule):
     """Power-of-two scales keep every product and partial sum exact in fp32."""
     rng = np.random.default_rng(6)
     M, N, K, g = 96, 72, 256, 64
@@ -163,9 +173,10 @@ def test_w4a4_power_of_two_scales_exact():
 
 @pytest.mark.parametrize("M,N,K,r,g,use_bias", [
     (200, 136, 320, 64, 64, True), (130, 129, 288, 32, 32, False), (64, 64, 256, 128, 128, True),
-    (77, 40, 128, 128, 32, False), (300, 264, 1152, 64, 64, False),
+    (77, 40, 128, 128, 32, False), (300, 264, 1152, 64, 64, False), (150, 300, 416, 32, 128, True),
+    (260, 515, 224, 96, 32, True),
 ])
-def test_w4a4_gemm_matches_oracle_on_identical_inputs(M, N, K, r, g, use_bias):
+def test_w4a4_gemm_matches_oracle_on_identical_inputs(M, N, K, r, g, use_bias, schedule):
     """Same x_h, codes, scales and weights on both sides.  fp32 accumulation of at most
     G + r/16 partial terms against a float64 sum: 1e-5 of the largest output magnitude
     per element is ample (observed ~1e-6); bf16 output equals the rounded fp32 output
@@ -193,6 +204,35 @@ def test_w4a4_gemm_matches_oracle_on_identical_inputs(M, N, K, r, g, use_bias):
     a = host_bf16_bits(yb).astype(np.int32)
     np.testing.assert_array_equal(a, O.bf16_bits(O.round_to_bf16(yf)).astype(np.int32))   # own rounding is RNE
     assert np.abs(O.from_bf16_bits(host_bf16_bits(yb)) - ybf).max() <= 2.0 ** -7 * scale
+
+
+def test_w4a4_persistent_workgroups_take_several_tiles(monkeypatch):
+    """300 tiles of 256 x 128 on 256 CUs: some workgroups of the persistent schedule run two tiles back to back
+    (the stage stream crosses the tile boundary).  Ragged in both directions; a rank-32 branch, so the 16-bit
+    phase has padding stages."""
+    monkeypatch.setenv("DIROTQ_W4A4_KERNEL", "ws")
+    M, N, K, r, g = 2500, 3592, 224, 32, 64
+    _say(f"w4a4 persistent M={M} N={N} K={K} r={r} g={g}")
+    rng = np.random.default_rng(11)
+    G = (K - r) // g
+    xh = O.round_to_bf16(rng.standard_normal((M, r)).astype(np.float32) * 20)
+    Wh = O.round_to_bf16(rng.standard_normal((N, r)).astype(np.float32) * 0.05)
+    qx = rng.integers(-7, 8, size=(M, K - r)).astype(np.int8)
+    qw = rng.integers(-7, 8, size=(N, K - r)).astype(np.int8)
+    sx = rng.lognormal(-1, 1, size=(M, G)).astype(np.float16)
+    sw = rng.lognormal(-5, 1, size=(N, G)).astype(np.float16)
+    bias = O.round_to_bf16(rng.standard_normal(N).astype(np.float32))
+    y32, ybf = O.combine(xh, qx, sx, Wh, qw, sw, g, bias)
+    blob = import_blob(Wh, qw, sw, N, K, r, g)
+    args = (dev_bf16(O.bf16_bits(xh)), dev(pack_codes(qx)), dev(np.ascontiguousarray(sx.T)), blob, M, N, K, r, g)
+    bias_d = dev_bf16(O.bf16_bits(bias))
+    yf = B.w4a4_gemm(*args, bias=bias_d, out_dtype=torch.float32).cpu().numpy()
+    yb = B.w4a4_gemm(*args, bias=bias_d, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    scale = np.abs(y32).max()
+    assert np.abs(yf - y32).max() <= 1e-5 * scale
+    np.testing.assert_array_equal(host_bf16_bits(yb).astype(np.int32),
+                                  O.bf16_bits(O.round_to_bf16(yf)).astype(np.int32))
 
 
 # ------------------------------------------------------------------ end to end

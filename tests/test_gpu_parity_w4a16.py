@@ -121,3 +121,30 @@ def test_w4a16_empty():
     blob = _blob(qw, np.ones((8, 2), np.float16), 8, 64, 32)
     y = B.w4a16_gemm(torch.empty((0, 64), dtype=torch.bfloat16, device="cuda"), blob, 8, 32)
     assert y.shape == (0, 8)
+
+
+def test_w4a16_same_rows_through_every_kernel_choice():
+    """The launcher picks a kernel from the token count (few-token kernel up to 32 tokens, the same kernel per
+    slice of 32 tokens where a cost model prefers it, the 128 x 128 tiling otherwise).  The same 32 rows are
+    sent in calls of 32, 33, 64 and 600 tokens (K = N = 1152: one few-token launch; 32 + 1; two slices; tiles):
+    every choice agrees with the oracle, and with the others up to the order of fp32 additions -- results are
+    not bit-stable across token counts, which the header does not promise either."""
+    K = N = 1152
+    g = 64
+    rng = np.random.default_rng(58)
+    x = O.round_to_bf16((rng.standard_normal((600, K)) * rng.lognormal(0, 1, size=(1, K))).astype(np.float32))
+    qw = rng.integers(-7, 8, size=(N, K)).astype(np.int8)
+    sw = rng.lognormal(-4, 0.7, size=(N, K // g)).astype(np.float16)
+    blob = _blob(qw, sw, N, K, g)
+    y32, _ = O.linear_w4a16(x, qw, sw, g)
+    scale = np.abs(y32).max()
+    xd = dev_bf16(O.bf16_bits(x))
+    outs = {}
+    for M in (32, 33, 64, 600):
+        _say(f"w4a16 kernel choice M={M}")
+        y = B.w4a16_gemm(xd[:M].contiguous(), blob, N, g, out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        outs[M] = y.cpu().numpy()
+        assert np.abs(outs[M] - y32[:M]).max() <= 1e-5 * scale
+    for M in (33, 64, 600):
+        assert np.abs(outs[M][:32] - outs[32]).max() <= 2e-5 * scale
