@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdirotq.so")
 PROBE_LIB = os.path.join(HERE, "libdirotq_probe.so")     # matrix-pipe rate probes used by bench.py only
-SOURCES = ["dirotq_abi.hip", "rotate_quantize.hip", "w4a4_gemm.hip", "w4a4_gemm_ws.hip", "w4a8_gemm.hip", "w4a16_gemm.hip", "prepare.hip"]
+SOURCES = ["dirotq_abi.hip", "rotate_quantize.hip", "w4a4_gemm.hip", "w4a4_gemm_ws.hip", "w4a4_gemm_skinny.hip", "w4a8_gemm.hip", "w4a16_gemm.hip", "prepare.hip"]
 
 # packed-fp32 VALU instructions are switched off on purpose (they have produced wrong
 # results on the test machines); no fast-math: the quantizer relies on IEEE division.

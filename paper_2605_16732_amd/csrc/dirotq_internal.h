@@ -107,6 +107,10 @@ int launch_w4a4_gemm(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, 
 // symmetric activation codes only; 4-bit part not empty (wave-specialised schedule of the same arithmetic)
 int launch_w4a4_gemm_ws(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const void* blob,
                         const uint16_t* bias, int M, int N, int K, int r, int g, void* y, int y_dtype, hipStream_t s);
+// symmetric activation codes, few tokens: the K axis split over the waves of a workgroup (64 x 64 outputs each)
+int launch_w4a4_gemm_skinny(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const void* blob,
+                            const uint16_t* bias, int M, int N, int K, int r, int g, void* y, int y_dtype,
+                            hipStream_t s);
 int launch_prepare_rotation(const float* Q, int K, uint16_t* Qt, hipStream_t s);
 int launch_prepare_weights(const float* W, const float* Q, int N, int K, int r, int g, void* blob,
                            float* scratch, hipStream_t s);

@@ -52,6 +52,140 @@ struct RQ {
   __device__ static __forceinline__ int swz(int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
 };
 
+// Epilogue of a wave whose accumulators are 4 x WT tiles of 32 channels x 32 tokens (32x32 MFMA layout: a lane
+// owns one token and 4 consecutive channels per register quad): the split at r, the per-group quantizer and the
+// packing, all in registers.  vb: the wave's first virtual channel (the 16-bit part padded to a multiple of 128,
+// then the 4-bit part); tok_base: its first token.
+template <int QM, int WT>
+__device__ __forceinline__ void rq_epilogue32(const f32x16 (&acc)[4][WT], int vb, int tok_base, int M, int K, int r,
+                                              int g, int r_pad, int Kv, uint16_t* __restrict__ xh,
+                                              uint8_t* __restrict__ xl, uint16_t* __restrict__ sx,
+                                              uint16_t* __restrict__ zx, float* __restrict__ xf,
+                                              float* __restrict__ pmax, int sx_ld) {
+  constexpr bool ASYM = QM == 1;
+  const int l = threadIdx.x & 63;
+  if (vb >= Kv) return;
+  const int h = l >> 5;
+  if (vb < r_pad) {
+    // 16-bit part: 4 consecutive channels per register quad -> one 8-byte store
+#pragma unroll
+    for (int j = 0; j < WT; j++) {
+      const int m = tok_base + j * 32 + (l & 31);
+#pragma unroll
+      for (int i = 0; i < 4; i++)
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+          const int c = vb + i * 32 + 8 * q + 4 * h;
+          if (c < r && m < M) {
+            uint2 o;
+            o.x = f32_to_bf16_bits(acc[i][j][4 * q]) | ((uint32_t)f32_to_bf16_bits(acc[i][j][4 * q + 1]) << 16);
+            o.y = f32_to_bf16_bits(acc[i][j][4 * q + 2]) | ((uint32_t)f32_to_bf16_bits(acc[i][j][4 * q + 3]) << 16);
+            *(uint2*)(xh + (size_t)m * r + c) = o;
+          }
+        }
+    }
+    return;
+  }
+  const int cl0 = vb - r_pad;                               // first 4-bit channel of this wave
+  const int KL = K - r;
+  if constexpr (QM == 2) {
+    // raw fp32 values (16-byte stores) and the wave tile's absolute maximum per token
+#pragma unroll
+    for (int j = 0; j < WT; j++) {
+      const int m = tok_base + j * 32 + (l & 31);
+      float a = 0.0f;
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        const int cl = cl0 + i * 32;
+        if (cl < KL) {
+#pragma unroll
+          for (int v = 0; v < 16; v++) a = fmaxf(a, fabsf(acc[i][j][v]));
+          if (m < M) {
+#pragma unroll
+            for (int q = 0; q < 4; q++)
+              *(float4*)(xf + (size_t)m * KL + cl + 8 * q + 4 * h) =
+                  make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+          }
+        }
+      }
+      a = fmaxf(a, __shfl_xor(a, 32));
+      if (h == 0 && m < M) pmax[(size_t)(cl0 >> 7) * sx_ld + m] = a;
+    }
+    return;
+  }
+  const size_t xl_ld = (size_t)KL / 2;
+  const int gi_tiles = g >> 5;                              // 32-channel MFMA tiles per group: 1, 2, 4
+#pragma unroll
+  for (int j = 0; j < WT; j++) {
+    const int m = tok_base + j * 32 + (l & 31);
+    // absmax (symmetric) or min and max (asymmetric) of each 32-channel tile over the lane
+    // pair, then combined per group
+    float tmax[4], tmin[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      if constexpr (ASYM) {
+        float lo = acc[i][j][0], hi = acc[i][j][0];
+#pragma unroll
+        for (int v = 1; v < 16; v++) {
+          lo = fminf(lo, acc[i][j][v]);
+          hi = fmaxf(hi, acc[i][j][v]);
+        }
+        tmin[i] = fminf(lo, __shfl_xor(lo, 32));
+        tmax[i] = fmaxf(hi, __shfl_xor(hi, 32));
+      } else {
+        float a = 0.0f;
+#pragma unroll
+        for (int v = 0; v < 16; v++) a = fmaxf(a, fabsf(acc[i][j][v]));
+        tmax[i] = fmaxf(a, __shfl_xor(a, 32));
+        tmin[i] = 0.0f;
+      }
+    }
+    if (gi_tiles == 2) {
+      tmax[0] = tmax[1] = fmaxf(tmax[0], tmax[1]);
+      tmax[2] = tmax[3] = fmaxf(tmax[2], tmax[3]);
+      tmin[0] = tmin[1] = fminf(tmin[0], tmin[1]);
+      tmin[2] = tmin[3] = fminf(tmin[2], tmin[3]);
+    } else if (gi_tiles == 4) {
+      tmax[0] = tmax[1] = tmax[2] = tmax[3] = fmaxf(fmaxf(tmax[0], tmax[1]), fmaxf(tmax[2], tmax[3]));
+      tmin[0] = tmin[1] = tmin[2] = tmin[3] = fminf(fminf(tmin[0], tmin[1]), fminf(tmin[2], tmin[3]));
+    }
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const int cl = cl0 + i * 32;                          // first 4-bit channel of this tile
+      const bool valid = cl < KL && m < M;
+      uint16_t sbits, zbits = 0;
+      float sf, zf = 0.0f;
+      if constexpr (ASYM) {
+        zf = group_zero(tmin[i], zbits);
+        sf = group_scale_asym(tmin[i], tmax[i], sbits);
+      } else {
+        sf = group_scale(tmax[i], sbits);
+      }
+      const float inv = group_inv(sf);
+      if (valid && h == 0 && (i % gi_tiles) == 0) {
+        sx[(size_t)(cl / g) * sx_ld + m] = sbits;
+        if constexpr (ASYM) zx[(size_t)(cl / g) * sx_ld + m] = zbits;
+      }
+      auto nib = [&](float v) { return ASYM ? quant_nibble_asym(v, zf, inv) : quant_nibble(v, inv); };
+      // this lane's 16 codes: quad q covers channels cl + 8q + 4h .. +3 -> one 16-bit piece
+      uint32_t piece[4];
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        piece[q] = nib(acc[i][j][4 * q]) | nib(acc[i][j][4 * q + 1]) << 4 | nib(acc[i][j][4 * q + 2]) << 8 |
+                   nib(acc[i][j][4 * q + 3]) << 12;
+      }
+      const uint32_t P0 = piece[0] | (piece[1] << 16), P1 = piece[2] | (piece[3] << 16);
+      // lane h=0 keeps dwords 0,1 of the tile's 16 bytes, lane h=1 dwords 2,3
+      const uint32_t recv = __shfl_xor(h ? P0 : P1, 32);
+      const uint32_t lo = h ? recv : P0, hi = h ? P1 : recv;
+      uint2 o;
+      o.x = (lo & 0xFFFFu) | (hi << 16);
+      o.y = (lo >> 16) | (hi & 0xFFFF0000u);
+      if (valid) *(uint2*)(xl + (size_t)m * xl_ld + cl / 2 + 8 * h) = o;
+    }
+  }
+}
+
 // QM selects what happens to the channels [r, K): 0 = symmetric 4-bit per-group quantizer,
 // 1 = asymmetric one (zero-point min, 16 unsigned levels; zx receives the zero-points, laid out
 // like sx), 2 = no quantizer here: the fp32 values go to xf [M][K-r] and the absolute maximum of
@@ -184,127 +318,8 @@ __global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK>::WAVES_PER_SIMD)) 
     } while (++kt < nk);
 
     // ---- epilogue, in registers ------------------------------------------------------
-    const int vb = ct * C::TC + wc * 128;                     // first virtual channel of this wave
-    if (vb >= Kv) return;
-    const int h = l >> 5;
-    if (vb < r_pad) {
-      // 16-bit part: 4 consecutive channels per register quad -> one 8-byte store
-#pragma unroll
-      for (int j = 0; j < WT; j++) {
-        const int m = m0 + wt * C::WAVE_T + j * 32 + (l & 31);
-#pragma unroll
-        for (int i = 0; i < 4; i++)
-#pragma unroll
-          for (int q = 0; q < 4; q++) {
-            const int c = vb + i * 32 + 8 * q + 4 * h;
-            if (c < r && m < M) {
-              uint2 o;
-              o.x = f32_to_bf16_bits(acc[i][j][4 * q]) | ((uint32_t)f32_to_bf16_bits(acc[i][j][4 * q + 1]) << 16);
-              o.y = f32_to_bf16_bits(acc[i][j][4 * q + 2]) | ((uint32_t)f32_to_bf16_bits(acc[i][j][4 * q + 3]) << 16);
-              *(uint2*)(xh + (size_t)m * r + c) = o;
-            }
-          }
-      }
-      return;
-    }
-    const int cl0 = vb - r_pad;                               // first 4-bit channel of this wave
-    const int KL = K - r;
-    if constexpr (QM == 2) {
-      // raw fp32 values (16-byte stores) and the wave tile's absolute maximum per token
-#pragma unroll
-      for (int j = 0; j < WT; j++) {
-        const int m = m0 + wt * C::WAVE_T + j * 32 + (l & 31);
-        float a = 0.0f;
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-          const int cl = cl0 + i * 32;
-          if (cl < KL) {
-#pragma unroll
-            for (int v = 0; v < 16; v++) a = fmaxf(a, fabsf(acc[i][j][v]));
-            if (m < M) {
-#pragma unroll
-              for (int q = 0; q < 4; q++)
-                *(float4*)(xf + (size_t)m * KL + cl + 8 * q + 4 * h) =
-                    make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-            }
-          }
-        }
-        a = fmaxf(a, __shfl_xor(a, 32));
-        if (h == 0 && m < M) pmax[(size_t)(cl0 >> 7) * sx_ld + m] = a;
-      }
-      return;
-    }
-    const size_t xl_ld = (size_t)KL / 2;
-    const int gi_tiles = g >> 5;                              // 32-channel MFMA tiles per group: 1, 2, 4
-#pragma unroll
-    for (int j = 0; j < WT; j++) {
-      const int m = m0 + wt * C::WAVE_T + j * 32 + (l & 31);
-      // absmax (symmetric) or min and max (asymmetric) of each 32-channel tile over the lane
-      // pair, then combined per group
-      float tmax[4], tmin[4];
-#pragma unroll
-      for (int i = 0; i < 4; i++) {
-        if constexpr (ASYM) {
-          float lo = acc[i][j][0], hi = acc[i][j][0];
-#pragma unroll
-          for (int v = 1; v < 16; v++) {
-            lo = fminf(lo, acc[i][j][v]);
-            hi = fmaxf(hi, acc[i][j][v]);
-          }
-          tmin[i] = fminf(lo, __shfl_xor(lo, 32));
-          tmax[i] = fmaxf(hi, __shfl_xor(hi, 32));
-        } else {
-          float a = 0.0f;
-#pragma unroll
-          for (int v = 0; v < 16; v++) a = fmaxf(a, fabsf(acc[i][j][v]));
-          tmax[i] = fmaxf(a, __shfl_xor(a, 32));
-          tmin[i] = 0.0f;
-        }
-      }
-      if (gi_tiles == 2) {
-        tmax[0] = tmax[1] = fmaxf(tmax[0], tmax[1]);
-        tmax[2] = tmax[3] = fmaxf(tmax[2], tmax[3]);
-        tmin[0] = tmin[1] = fminf(tmin[0], tmin[1]);
-        tmin[2] = tmin[3] = fminf(tmin[2], tmin[3]);
-      } else if (gi_tiles == 4) {
-        tmax[0] = tmax[1] = tmax[2] = tmax[3] = fmaxf(fmaxf(tmax[0], tmax[1]), fmaxf(tmax[2], tmax[3]));
-        tmin[0] = tmin[1] = tmin[2] = tmin[3] = fminf(fminf(tmin[0], tmin[1]), fminf(tmin[2], tmin[3]));
-      }
-#pragma unroll
-      for (int i = 0; i < 4; i++) {
-        const int cl = cl0 + i * 32;                          // first 4-bit channel of this tile
-        const bool valid = cl < KL && m < M;
-        uint16_t sbits, zbits = 0;
-        float sf, zf = 0.0f;
-        if constexpr (ASYM) {
-          zf = group_zero(tmin[i], zbits);
-          sf = group_scale_asym(tmin[i], tmax[i], sbits);
-        } else {
-          sf = group_scale(tmax[i], sbits);
-        }
-        const float inv = group_inv(sf);
-        if (valid && h == 0 && (i % gi_tiles) == 0) {
-          sx[(size_t)(cl / g) * sx_ld + m] = sbits;
-          if constexpr (ASYM) zx[(size_t)(cl / g) * sx_ld + m] = zbits;
-        }
-        auto nib = [&](float v) { return ASYM ? quant_nibble_asym(v, zf, inv) : quant_nibble(v, inv); };
-        // this lane's 16 codes: quad q covers channels cl + 8q + 4h .. +3 -> one 16-bit piece
-        uint32_t piece[4];
-#pragma unroll
-        for (int q = 0; q < 4; q++) {
-          piece[q] = nib(acc[i][j][4 * q]) | nib(acc[i][j][4 * q + 1]) << 4 | nib(acc[i][j][4 * q + 2]) << 8 |
-                     nib(acc[i][j][4 * q + 3]) << 12;
-        }
-        const uint32_t P0 = piece[0] | (piece[1] << 16), P1 = piece[2] | (piece[3] << 16);
-        // lane h=0 keeps dwords 0,1 of the tile's 16 bytes, lane h=1 dwords 2,3
-        const uint32_t recv = __shfl_xor(h ? P0 : P1, 32);
-        const uint32_t lo = h ? recv : P0, hi = h ? P1 : recv;
-        uint2 o;
-        o.x = (lo & 0xFFFFu) | (hi << 16);
-        o.y = (lo >> 16) | (hi & 0xFFFF0000u);
-        if (valid) *(uint2*)(xl + (size_t)m * xl_ld + cl / 2 + 8 * h) = o;
-      }
-    }
+    rq_epilogue32<QM, WT>(acc, ct * C::TC + wc * 128, m0 + wt * C::WAVE_T, M, K, r, g, r_pad, Kv, xh, xl, sx, zx, xf,
+                          pmax, sx_ld);
   } else {
     // ======== 16x16x32 MFMA: wave tile = 8 x 4 tiles of 16 channels x 16 tokens =========
     // Accumulator layout of a 16x16 tile: lane l holds channels 4*(l/16) .. +3 of token l%16, so

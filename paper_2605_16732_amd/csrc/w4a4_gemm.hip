@@ -435,19 +435,25 @@ static int launch_one(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx,
   return e == hipSuccess ? DIROTQ_OK : hip_failed(e);
 }
 
-// Which of the two schedules runs a symmetric layer.  The wave-specialised kernel (persistent workgroups, one per
-// CU, 256 x 128 tiles) is the faster one per tile; the kernel in this file (128 x 128 tiles, two workgroups per
-// CU) spreads a small problem over more CUs.  Measured crossover: about 128 of the larger tiles.
-// DIROTQ_W4A4_KERNEL=ws / tile in the environment forces one of them wherever it applies (the tests use it to run
-// both on the same inputs).
-static bool w4a4_ws_preferred(int M, int N, int K, int r) {
-  if (K - r <= 0) return false;
+// Which of the three schedules runs a symmetric layer.  The wave-specialised kernel (persistent workgroups, one
+// per CU, 256 x 128 tiles) is the fastest per tile; the kernel in this file (128 x 128 tiles, two workgroups per
+// CU) spreads a medium problem over more CUs; with few tokens both leave most of the chip idle and the split-K
+// kernel (64 x 64 outputs per workgroup, the K axis over its 8 waves) is the one with the shortest latency.
+// Measured crossovers: about 128 of the 256 x 128 tiles; about 288 of the 64 x 64 ones (512 from K = 2048 on).
+// DIROTQ_W4A4_KERNEL=ws / tile / skinny in the environment forces one of them wherever it applies (the tests use
+// it to run all of them on the same inputs).
+enum class W4A4Schedule { kTile, kWs, kSkinny };
+static W4A4Schedule w4a4_schedule(int M, int N, int K, int r) {
+  if (K - r <= 0) return W4A4Schedule::kTile;
   if (const char* f = getenv("DIROTQ_W4A4_KERNEL")) {
-    if (!strcmp(f, "ws")) return true;
-    if (!strcmp(f, "tile")) return false;
+    if (!strcmp(f, "ws")) return W4A4Schedule::kWs;
+    if (!strcmp(f, "tile")) return W4A4Schedule::kTile;
+    if (!strcmp(f, "skinny")) return W4A4Schedule::kSkinny;
   }
-  const long tiles = (long)((M + 127) / 128) * ((N + 255) / 256);
-  return tiles >= 128;
+  const long big = (long)((M + 127) / 128) * ((N + 255) / 256);
+  if (big >= 128) return W4A4Schedule::kWs;
+  const long small = (long)((M + 63) / 64) * ((N + 63) / 64);
+  return (small <= 288 || (small <= 512 && K >= 2048)) ? W4A4Schedule::kSkinny : W4A4Schedule::kTile;
 }
 
 int launch_w4a4_gemm(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const uint16_t* zx,
@@ -460,8 +466,12 @@ int launch_w4a4_gemm(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, 
                      : launch_one<GS, false, true>(xh, xl, sx, zx, blob, bias, M, N, K, r, y, s);     \
     return y_dtype ? launch_one<GS, true, false>(xh, xl, sx, zx, blob, bias, M, N, K, r, y, s)        \
                    : launch_one<GS, false, false>(xh, xl, sx, zx, blob, bias, M, N, K, r, y, s);
-  if (!zx && w4a4_ws_preferred(M, N, K, r))
-    return launch_w4a4_gemm_ws(xh, xl, sx, blob, bias, M, N, K, r, g, y, y_dtype, s);
+  if (!zx) {
+    const W4A4Schedule sch = w4a4_schedule(M, N, K, r);
+    if (sch == W4A4Schedule::kWs) return launch_w4a4_gemm_ws(xh, xl, sx, blob, bias, M, N, K, r, g, y, y_dtype, s);
+    if (sch == W4A4Schedule::kSkinny)
+      return launch_w4a4_gemm_skinny(xh, xl, sx, blob, bias, M, N, K, r, g, y, y_dtype, s);
+  }
   switch (g) {
     DIROTQ_CASE(32)
     DIROTQ_CASE(64)

@@ -123,11 +123,12 @@ def test_rotate_quantize_ties_and_clip():
 
 
 # ------------------------------------------------------------------ kernel B, exact
-@pytest.fixture(params=["tile", "ws"])
+@pytest.fixture(params=["tile", "ws", "skinny"])
 def schedule(request, monkeypatch):
-    """Kernel B has two schedules of the same arithmetic (128 x 128 tiles, two workgroups per CU; persistent
-    wave-specialised workgroups on 256 x 128 tiles); the library picks by problem size.  The environment switch
-    read at every launch forces one, so that both run on the same inputs."""
+    """Kernel B has three schedules of the same arithmetic (128 x 128 tiles, two workgroups per CU; persistent
+    wave-specialised workgroups on 256 x 128 tiles; 64 x 64 outputs per workgroup with the K axis split over its
+    waves, for few tokens); the library picks by problem size.  The environment switch read at every launch
+    forces one, so that all of them run on the same inputs."""
     monkeypatch.setenv("DIROTQ_W4A4_KERNEL", request.param)
     return request.param
 
