@@ -26,9 +26,10 @@
 
 namespace dirotq {
 
-template <int WGC, int WGT, int BK>
+template <int WGC, int WGT, int BK, int WVT = 64>
 struct RQ {
-  static constexpr int WAVE_C = 128, WAVE_T = 64;          // wave tile: channels x tokens
+  static constexpr int WAVE_C = 128, WAVE_T = WVT;         // wave tile: channels x tokens (64, or 32 for the
+                                                           // small launches: half the arithmetic per wave and stage)
   static constexpr int TC = WGC * WAVE_C, TT = WGT * WAVE_T;
   static constexpr int NW = WGC * WGT, NT = NW * 64;
   static constexpr int ROWB = BK * 2;                      // bytes per LDS row
@@ -191,12 +192,13 @@ __device__ __forceinline__ void rq_epilogue32(const f32x16 (&acc)[4][WT], int vb
 // like sx), 2 = no quantizer here: the fp32 values go to xf [M][K-r] and the absolute maximum of
 // every 128-channel wave tile to pmax [ceil((K-r)/128)][M] (per-token 8-bit quantization needs the
 // maximum over all channels of a token, which no single workgroup sees).
-template <int WGC, int WGT, int BK, int MI, int QM>
-__global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK>::WAVES_PER_SIMD)) void rotate_quantize_kernel(
+template <int WGC, int WGT, int BK, int MI, int QM, int WVT>
+__global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK, WVT>::WAVES_PER_SIMD)) void rotate_quantize_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ Qt, int M, int K, int r, int g,
     uint16_t* __restrict__ xh, uint8_t* __restrict__ xl, uint16_t* __restrict__ sx, uint16_t* __restrict__ zx,
     float* __restrict__ xf, float* __restrict__ pmax, int r_pad, int Kv, int n_ct, int n_tt, int per_xcd, int sx_ld) {
-  using C = RQ<WGC, WGT, BK>;
+  using C = RQ<WGC, WGT, BK, WVT>;
+  static_assert(WVT == 64 || (WVT == 32 && MI == 32), "32-token wave tiles are written for the 32x32 loop only");
   constexpr bool ASYM = QM == 1;
   extern __shared__ __align__(16) unsigned char smem[];
 
@@ -262,7 +264,7 @@ __global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK>::WAVES_PER_SIMD)) 
 
   if constexpr (MI == 32) {
     // ======== 32x32x16 MFMA: wave tile = 4 x 2 tiles of 32 channels x 32 tokens ========
-    constexpr int WT = 2;                                     // 32-token MFMA tiles per wave
+    constexpr int WT = C::WAVE_T / 32;                        // 32-token MFMA tiles per wave
     f32x16 acc[4][WT];
 #pragma unroll
     for (int i = 0; i < 4; i++)
@@ -557,7 +559,7 @@ __global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK>::WAVES_PER_SIMD)) 
   }
 }
 
-template <int WGC, int WGT, int BK, int MI, int QM>
+template <int WGC, int WGT, int BK, int MI, int QM, int WVT>
 static int launch_one(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g, uint16_t* xh,
                       uint8_t* xl, uint16_t* sx, uint16_t* zx, float* xf, float* pmax, hipStream_t s, int m_off,
                       int sx_ld) {
@@ -570,7 +572,7 @@ static int launch_one(const uint16_t* x, const uint16_t* Qt, int M, int K, int r
   if (zx) zx += m_off;
   if (xf) xf += (size_t)m_off * (K - r);
   if (pmax) pmax += m_off;
-  using C = RQ<WGC, WGT, BK>;
+  using C = RQ<WGC, WGT, BK, WVT>;
   const int r_pad = (r + 127) / 128 * 128;
   const int Kv = r_pad + (K - r + 127) / 128 * 128;
   const int n_ct = (Kv + C::TC - 1) / C::TC;
@@ -580,29 +582,31 @@ static int launch_one(const uint16_t* x, const uint16_t* Qt, int M, int K, int r
   // (idempotent: two threads racing here would both set the same attribute)
   static std::atomic<bool> attr_done{false};
   if (!attr_done.load(std::memory_order_acquire)) {
-    hipError_t e = hipFuncSetAttribute((const void*)rotate_quantize_kernel<WGC, WGT, BK, MI, QM>,
+    hipError_t e = hipFuncSetAttribute((const void*)rotate_quantize_kernel<WGC, WGT, BK, MI, QM, WVT>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
     if (e != hipSuccess) return hip_failed(e);
     attr_done.store(true, std::memory_order_release);
   }
-  hipLaunchKernelGGL((rotate_quantize_kernel<WGC, WGT, BK, MI, QM>), dim3(per_xcd * 8), dim3(C::NT), C::SMEM, s, x,
+  hipLaunchKernelGGL((rotate_quantize_kernel<WGC, WGT, BK, MI, QM, WVT>), dim3(per_xcd * 8), dim3(C::NT), C::SMEM, s, x,
                      Qt, M, K, r, g, xh, xl, sx, zx, xf, pmax, r_pad, Kv, n_ct, n_tt, per_xcd, sx_ld);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? DIROTQ_OK : hip_failed(e);
 }
 
-template <int WGC, int WGT, int BK, int MI>
+template <int WGC, int WGT, int BK, int MI, int WVT = 64>
 static int launch_cfg(const RqOut& o, const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g,
                       hipStream_t s, int m_off = 0, int sx_ld = 0) {
-  if (o.xf) return launch_one<WGC, WGT, BK, MI, 2>(x, Qt, M, K, r, g, o.xh, o.xl, o.sx, o.zx, o.xf, o.pmax, s, m_off, sx_ld);
-  if (o.zx) return launch_one<WGC, WGT, BK, MI, 1>(x, Qt, M, K, r, g, o.xh, o.xl, o.sx, o.zx, o.xf, o.pmax, s, m_off, sx_ld);
-  return launch_one<WGC, WGT, BK, MI, 0>(x, Qt, M, K, r, g, o.xh, o.xl, o.sx, o.zx, o.xf, o.pmax, s, m_off, sx_ld);
+  if (o.xf) return launch_one<WGC, WGT, BK, MI, 2, WVT>(x, Qt, M, K, r, g, o.xh, o.xl, o.sx, o.zx, o.xf, o.pmax, s, m_off, sx_ld);
+  if (o.zx) return launch_one<WGC, WGT, BK, MI, 1, WVT>(x, Qt, M, K, r, g, o.xh, o.xl, o.sx, o.zx, o.xf, o.pmax, s, m_off, sx_ld);
+  return launch_one<WGC, WGT, BK, MI, 0, WVT>(x, Qt, M, K, r, g, o.xh, o.xl, o.sx, o.zx, o.xf, o.pmax, s, m_off, sx_ld);
 }
 
 int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g, const RqOut& o,
                            hipStream_t s) {
   // Large problems: 256 x 256 workgroup tiles (8 waves); medium: 256 channels x 128 tokens
-  // (4 waves); small: 128 x 128 (2 waves), so that the grid still covers the chip.
+  // (4 waves); small: 128 x 128 as 4 waves of 128 channels x 32 tokens.  A small launch is a chain of
+  // latencies (a few dozen workgroups, each alone on its CU, walk K stage by stage), so its waves carry
+  // half the arithmetic per stage: 13 instead of 20 us at M = 256, K = 1152.
   // The large tiles run long enough to be limited by power (the shader clock drops under
   // sustained MFMA work on random data); there the 16x16x32 MFMA, which moves half the
   // accumulator bytes per multiply-add, is the faster one.  The smaller, latency-bound
@@ -614,7 +618,7 @@ int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, 
   const long mid_tiles = n_tc256 * ((M + 127) / 128);    // 256 channels x 128 tokens
   if (K % 64 != 0) {
     if (mid_tiles >= 100) return launch_cfg<2, 2, 32, 32>(o, x, Qt, M, K, r, g, s);
-    return launch_cfg<1, 2, 32, 32>(o, x, Qt, M, K, r, g, s);
+    return launch_cfg<1, 4, 32, 32, 32>(o, x, Qt, M, K, r, g, s);
   }
   if (big_tiles >= 200) {
     // 256 CUs take one big tile each per round.  When the last round would be less than 40-60%
@@ -631,7 +635,7 @@ int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, 
     return launch_cfg<2, 4, 64, 16>(o, x, Qt, M, K, r, g, s);
   }
   if (mid_tiles >= 100) return launch_cfg<2, 2, 64, 32>(o, x, Qt, M, K, r, g, s);
-  return launch_cfg<1, 2, 32, 32>(o, x, Qt, M, K, r, g, s);
+  return launch_cfg<1, 4, 64, 32, 32>(o, x, Qt, M, K, r, g, s);
 }
 
 }  // namespace dirotq
