@@ -16,6 +16,9 @@
 // through registers.
 #include <atomic>
 
+#include <cstdlib>
+#include <cstring>
+
 #include "gemm_tail.h"
 
 namespace dirotq {
@@ -458,6 +461,10 @@ int launch_w4a16_gemm(const uint16_t* x, const void* blob, const uint16_t* bias,
     return y_dtype ? launch_few16<64, true, 32>(xs, blob, bias, Ms, N, K, g, ys, s)
                    : launch_few16<64, false, 32>(xs, blob, bias, Ms, N, K, g, ys, s);
   };
+  // DIROTQ_W4A16_KERNEL=tile in the environment bars the few-token kernel above 32 tokens (the tests use it to
+  // run the same rows through both kernels whatever the cost model below says)
+  const char* force = getenv("DIROTQ_W4A16_KERNEL");
+  const bool force_tile = force && !strcmp(force, "tile");
   // few tokens: the weight stream, not the matrix pipe, is the bound
   if (M <= 32) return few(x, y, M);
   // A few hundred tokens leave the 128 x 128 tiling with less than one round of workgroups, each walking
@@ -469,7 +476,7 @@ int launch_w4a16_gemm(const uint16_t* x, const void* blob, const uint16_t* bias,
     const long tiles = (long)((M + TM - 1) / TM) * ((N + TN - 1) / TN);
     const double t_few = slices * ((double)N * K / 2 / 1.2e6 + 5.0);
     const double t_tiles = (K / 64.0) * 1.23 * (double)((tiles + 511) / 512);
-    if (slices <= 16 && t_few < t_tiles) {
+    if (!force_tile && slices <= 16 && t_few < t_tiles) {
       const size_t ybytes = y_dtype ? 4 : 2;
       for (int i = 0; i < slices; i++) {
         const int st = few(x + (size_t)i * 32 * K, (char*)y + (size_t)i * 32 * N * ybytes, min(32, M - 32 * i));

@@ -148,3 +148,32 @@ def test_w4a16_same_rows_through_every_kernel_choice():
         assert np.abs(outs[M] - y32[:M]).max() <= 1e-5 * scale
     for M in (33, 64, 600):
         assert np.abs(outs[M][:32] - outs[32]).max() <= 2e-5 * scale
+
+
+def test_w4a16_cost_model_override_runs_both_kernels_on_the_same_rows(monkeypatch):
+    """Between 33 and a few hundred tokens a cost model fitted to the FLUX shapes decides between slices of the
+    few-token kernel and the 128 x 128 tiling.  DIROTQ_W4A16_KERNEL=tile bars the slices, so the same calls run
+    through both kernels whatever the model says: each within 1e-5 of the output scale of the oracle, and within
+    2e-5 of each other (fp32 summation order)."""
+    K, N, g = 3072, 1152, 64
+    rng = np.random.default_rng(59)
+    x = O.round_to_bf16((rng.standard_normal((96, K)) * rng.lognormal(0, 1, size=(1, K))).astype(np.float32))
+    qw = rng.integers(-7, 8, size=(N, K)).astype(np.int8)
+    sw = rng.lognormal(-4, 0.7, size=(N, K // g)).astype(np.float16)
+    blob = _blob(qw, sw, N, K, g)
+    y32, _ = O.linear_w4a16(x, qw, sw, g)
+    scale = np.abs(y32).max()
+    xd = dev_bf16(O.bf16_bits(x))
+    for M in (33, 64, 96):
+        got = {}
+        for mode in ("default", "tile"):
+            if mode == "tile":
+                monkeypatch.setenv("DIROTQ_W4A16_KERNEL", "tile")
+            else:
+                monkeypatch.delenv("DIROTQ_W4A16_KERNEL", raising=False)
+            _say(f"w4a16 override M={M} mode={mode}")
+            y = B.w4a16_gemm(xd[:M].contiguous(), blob, N, g, out_dtype=torch.float32)
+            torch.cuda.synchronize()
+            got[mode] = y.cpu().numpy()
+            assert np.abs(got[mode] - y32[:M]).max() <= 1e-5 * scale
+        assert np.abs(got["default"] - got["tile"]).max() <= 2e-5 * scale
