@@ -52,6 +52,14 @@
  *    in bits 0-3 and channel 2i+1 in bits 4-7.  A nibble is the code q in [-7, 7] in
  *    sign-magnitude form: bit 3 = sign, bits 0-2 = |q|; zero is always 0x0.
  *  - Activation scales are group-major: s_x[j * M + m] for group j, token m.
+ *  - The GEMM calls pick one of several schedules of the same arithmetic from the problem
+ *    size (few tokens: K split over the waves of a workgroup; medium: 128 x 128 tiles;
+ *    large: persistent wave-specialised workgroups).  The fp32 additions of an output are
+ *    ordered differently in each, so a token's result is deterministic for a given
+ *    (M, N, K, r, g) but not bit-identical across different M.  For testing, the
+ *    environment variables DIROTQ_W4A4_KERNEL (ws | tile | skinny) and
+ *    DIROTQ_W4A16_KERNEL (tile) are read at every launch and force a schedule wherever
+ *    it applies; they are not needed in normal use.
  */
 #ifndef DIROTQ_H
 #define DIROTQ_H

@@ -35,7 +35,8 @@ constexpr int TNW = 256, TMW = 128;          // output channels x tokens per wor
 constexpr int ROWS = TNW + TMW;              // rows of a stage: weights, then tokens
 constexpr int SB = 64;                       // bytes per row and stage
 constexpr int NBUF = 4;                      // stages in the LDS ring
-constexpr int NSETS = 8;                     // stages of global loads in flight per staging thread
+constexpr int nsets(int gs) { return gs == 32 ? 4 : 8; }   // stages of global loads in flight per staging thread
+                                                           // (32-channel groups carry twice the scale registers)
 constexpr int NMULT = 8, NSTAGE = 4;         // multiplying / staging waves
 constexpr int NT = (NMULT + NSTAGE) * 64;
 constexpr int STAGE_BYTES = ROWS * SB;       // 24 KB
@@ -193,6 +194,7 @@ __global__ __launch_bounds__(NT, 1) void w4a4_gemm_ws_kernel(
 
     // register sets: one stage each.  Loads are straight-line code of one shape, whatever the stage's kind, so
     // that the count of loads in flight is exact and a store waits for its own set only.
+    constexpr int NSETS = nsets(GS);
     uint4 rg[NSETS][3];
     uint16_t rsw[NSETS][GPS], rsx[NSETS][GPS];
     auto gload = [&](int set) {                          // loads the cursor's stage, then moves the cursor on
