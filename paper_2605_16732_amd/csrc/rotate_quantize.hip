@@ -26,21 +26,25 @@
 
 namespace dirotq {
 
-template <int WGC, int WGT, int BK, int WVT = 64>
+// KSP = 2: the workgroup holds two such sets of waves, each with LDS stages of its own, and each walks one half of
+// K; the halves' accumulators are added through LDS before the epilogue (small launches: half as long a chain of
+// stage latencies).
+template <int WGC, int WGT, int BK, int WVT = 64, int KSP = 1>
 struct RQ {
   static constexpr int WAVE_C = 128, WAVE_T = WVT;         // wave tile: channels x tokens (64, or 32 for the
                                                            // small launches: half the arithmetic per wave and stage)
   static constexpr int TC = WGC * WAVE_C, TT = WGT * WAVE_T;
-  static constexpr int NW = WGC * WGT, NT = NW * 64;
+  static constexpr int NW = WGC * WGT, NT = NW * KSP * 64; // waves per k-part, threads per workgroup
   static constexpr int ROWB = BK * 2;                      // bytes per LDS row
   static constexpr int CPR = ROWB / 16;                    // 16-B chunks per row
   static constexpr int STAGE_BYTES = (TC + TT) * ROWB;
   static constexpr int IPW = (TC + TT) * CPR / 64 / NW;    // 16-B loads per lane per stage
   static constexpr int KS = BK / 16;                       // MFMA k-steps per stage
   static constexpr int PP = IPW / KS;                      // store/load pairs per k-step
-  static constexpr int SMEM = 2 * STAGE_BYTES;
+  static constexpr int SMEM = KSP * 2 * STAGE_BYTES;
   // register budget: two waves per SIMD unless LDS (160 KB per CU) admits only one 4-wave workgroup
-  static constexpr int WAVES_PER_SIMD = (NW <= 4 && 2 * SMEM > 160 * 1024) ? 1 : 2;
+  static constexpr int WAVES_PER_SIMD = (NW * KSP <= 4 && 2 * SMEM > 160 * 1024) ? 1 : 2;
+  static_assert(KSP == 1 || (KSP == 2 && SMEM >= NW * 64 * (WAVE_C * WAVE_T / 64) * 4), "the second part's accumulators pass through the stage buffers");
   static_assert((TC + TT) * CPR % (64 * NW) == 0, "loads must divide evenly over waves");
   static_assert(BK == 32 || BK == 64, "BK");
   static_assert(IPW % KS == 0 && PP >= 1 && PP <= 4, "store/load pairs are spread over the 4 MFMA rows of a k-step");
@@ -192,15 +196,16 @@ __device__ __forceinline__ void rq_epilogue32(const f32x16 (&acc)[4][WT], int vb
 // like sx), 2 = no quantizer here: the fp32 values go to xf [M][K-r] and the absolute maximum of
 // every 128-channel wave tile to pmax [ceil((K-r)/128)][M] (per-token 8-bit quantization needs the
 // maximum over all channels of a token, which no single workgroup sees).
-template <int WGC, int WGT, int BK, int MI, int QM, int WVT>
-__global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK, WVT>::WAVES_PER_SIMD)) void rotate_quantize_kernel(
+template <int WGC, int WGT, int BK, int MI, int QM, int WVT, int KSP>
+__global__ __launch_bounds__(WGC* WGT* KSP * 64, (RQ<WGC, WGT, BK, WVT, KSP>::WAVES_PER_SIMD)) void rotate_quantize_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ Qt, int M, int K, int r, int g,
     uint16_t* __restrict__ xh, uint8_t* __restrict__ xl, uint16_t* __restrict__ sx, uint16_t* __restrict__ zx,
     float* __restrict__ xf, float* __restrict__ pmax, int r_pad, int Kv, int n_ct, int n_tt, int per_xcd, int sx_ld) {
-  using C = RQ<WGC, WGT, BK, WVT>;
+  using C = RQ<WGC, WGT, BK, WVT, KSP>;
   static_assert(WVT == 64 || (WVT == 32 && MI == 32), "32-token wave tiles are written for the 32x32 loop only");
+  static_assert(KSP == 1 || MI == 32, "the K split is written for the 32x32 loop only");
   constexpr bool ASYM = QM == 1;
-  extern __shared__ __align__(16) unsigned char smem[];
+  extern __shared__ __align__(16) unsigned char smem_all[];
 
   // consecutive workgroup ids go to different XCDs; give each XCD a contiguous run of tiles
   const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
@@ -213,8 +218,10 @@ __global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK, WVT>::WAVES_PER_SI
   const int ct = grp * GC + in_grp % gc, tt = in_grp / gc;
   const int m0 = tt * C::TT;
 
-  const int t = threadIdx.x, l = t & 63, w = t >> 6;
+  const int t = threadIdx.x, l = t & 63;
+  const int w = (t >> 6) % C::NW, kp = (t >> 6) / C::NW;    // wave within its k-part, k-part
   const int wc = w % WGC, wt = w / WGC;
+  unsigned char* const smem = smem_all + kp * (2 * C::STAGE_BYTES);   // the k-part's own two stages
 
   // ---- per-lane source pointers of this wave's loads ---------------------------------
   // load q of wave w fills LDS bytes [(w*IPW+q)*1024, +1024) of a stage: rows are the TC
@@ -235,7 +242,7 @@ __global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK, WVT>::WAVES_PER_SI
     } else {
       base = x + (size_t)min(m0 + row - C::TC, M - 1) * K;
     }
-    gsrc[i] = base + logical_chunk * 8;
+    gsrc[i] = base + logical_chunk * 8 + kp * (K / KSP);
   }
   i32x4 staged[C::IPW];
   auto gload = [&](int q, int kt) { staged[q] = *(const i32x4*)(gsrc[q] + kt * BK); };
@@ -243,7 +250,7 @@ __global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK, WVT>::WAVES_PER_SI
     *(i32x4*)(smem + buf * C::STAGE_BYTES + (w * C::IPW + q) * 1024 + l * 16) = staged[q];
   };
 
-  const int nk = K / BK;                                    // the launcher guarantees K % BK == 0, nk >= 1
+  const int nk = K / (BK * KSP);                            // the launcher guarantees K % (BK KSP) == 0, nk >= 1
 
   // prologue: stage 0 into LDS, stage 1 into the registers.  Loads past the last stage re-read
   // it: unconditional loads keep the outstanding-load count the same in every iteration, so
@@ -318,6 +325,36 @@ __global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK, WVT>::WAVES_PER_SI
       }
       __syncthreads();   // stage kt+1 is complete in LDS; stage kt may be overwritten
     } while (++kt < nk);
+
+    if constexpr (KSP == 2) {
+      // the second k-part hands its sums to the first through the stage buffers (every wave has passed the
+      // loop's last barrier, so nothing reads them any more); the first adds them and goes on alone
+      float4* red = (float4*)smem_all + (size_t)w * (4 * WT * 4 * 64) + l;
+      if (kp == 1) {
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+          for (int j = 0; j < WT; j++)
+#pragma unroll
+            for (int q = 0; q < 4; q++)
+              red[((i * WT + j) * 4 + q) * 64] =
+                  make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+      }
+      __syncthreads();
+      if (kp == 1) return;
+#pragma unroll
+      for (int i = 0; i < 4; i++)
+#pragma unroll
+        for (int j = 0; j < WT; j++)
+#pragma unroll
+          for (int q = 0; q < 4; q++) {
+            const float4 v = red[((i * WT + j) * 4 + q) * 64];
+            acc[i][j][4 * q] += v.x;
+            acc[i][j][4 * q + 1] += v.y;
+            acc[i][j][4 * q + 2] += v.z;
+            acc[i][j][4 * q + 3] += v.w;
+          }
+    }
 
     // ---- epilogue, in registers ------------------------------------------------------
     rq_epilogue32<QM, WT>(acc, ct * C::TC + wc * 128, m0 + wt * C::WAVE_T, M, K, r, g, r_pad, Kv, xh, xl, sx, zx, xf,
@@ -559,7 +596,7 @@ __global__ __launch_bounds__(WGC* WGT * 64, (RQ<WGC, WGT, BK, WVT>::WAVES_PER_SI
   }
 }
 
-template <int WGC, int WGT, int BK, int MI, int QM, int WVT>
+template <int WGC, int WGT, int BK, int MI, int QM, int WVT, int KSP>
 static int launch_one(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g, uint16_t* xh,
                       uint8_t* xl, uint16_t* sx, uint16_t* zx, float* xf, float* pmax, hipStream_t s, int m_off,
                       int sx_ld) {
@@ -572,7 +609,7 @@ static int launch_one(const uint16_t* x, const uint16_t* Qt, int M, int K, int r
   if (zx) zx += m_off;
   if (xf) xf += (size_t)m_off * (K - r);
   if (pmax) pmax += m_off;
-  using C = RQ<WGC, WGT, BK, WVT>;
+  using C = RQ<WGC, WGT, BK, WVT, KSP>;
   const int r_pad = (r + 127) / 128 * 128;
   const int Kv = r_pad + (K - r + 127) / 128 * 128;
   const int n_ct = (Kv + C::TC - 1) / C::TC;
@@ -582,31 +619,32 @@ static int launch_one(const uint16_t* x, const uint16_t* Qt, int M, int K, int r
   // (idempotent: two threads racing here would both set the same attribute)
   static std::atomic<bool> attr_done{false};
   if (!attr_done.load(std::memory_order_acquire)) {
-    hipError_t e = hipFuncSetAttribute((const void*)rotate_quantize_kernel<WGC, WGT, BK, MI, QM, WVT>,
+    hipError_t e = hipFuncSetAttribute((const void*)rotate_quantize_kernel<WGC, WGT, BK, MI, QM, WVT, KSP>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
     if (e != hipSuccess) return hip_failed(e);
     attr_done.store(true, std::memory_order_release);
   }
-  hipLaunchKernelGGL((rotate_quantize_kernel<WGC, WGT, BK, MI, QM, WVT>), dim3(per_xcd * 8), dim3(C::NT), C::SMEM, s, x,
+  hipLaunchKernelGGL((rotate_quantize_kernel<WGC, WGT, BK, MI, QM, WVT, KSP>), dim3(per_xcd * 8), dim3(C::NT), C::SMEM, s, x,
                      Qt, M, K, r, g, xh, xl, sx, zx, xf, pmax, r_pad, Kv, n_ct, n_tt, per_xcd, sx_ld);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? DIROTQ_OK : hip_failed(e);
 }
 
-template <int WGC, int WGT, int BK, int MI, int WVT = 64>
+template <int WGC, int WGT, int BK, int MI, int WVT = 64, int KSP = 1>
 static int launch_cfg(const RqOut& o, const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g,
                       hipStream_t s, int m_off = 0, int sx_ld = 0) {
-  if (o.xf) return launch_one<WGC, WGT, BK, MI, 2, WVT>(x, Qt, M, K, r, g, o.xh, o.xl, o.sx, o.zx, o.xf, o.pmax, s, m_off, sx_ld);
-  if (o.zx) return launch_one<WGC, WGT, BK, MI, 1, WVT>(x, Qt, M, K, r, g, o.xh, o.xl, o.sx, o.zx, o.xf, o.pmax, s, m_off, sx_ld);
-  return launch_one<WGC, WGT, BK, MI, 0, WVT>(x, Qt, M, K, r, g, o.xh, o.xl, o.sx, o.zx, o.xf, o.pmax, s, m_off, sx_ld);
+  if (o.xf) return launch_one<WGC, WGT, BK, MI, 2, WVT, KSP>(x, Qt, M, K, r, g, o.xh, o.xl, o.sx, o.zx, o.xf, o.pmax, s, m_off, sx_ld);
+  if (o.zx) return launch_one<WGC, WGT, BK, MI, 1, WVT, KSP>(x, Qt, M, K, r, g, o.xh, o.xl, o.sx, o.zx, o.xf, o.pmax, s, m_off, sx_ld);
+  return launch_one<WGC, WGT, BK, MI, 0, WVT, KSP>(x, Qt, M, K, r, g, o.xh, o.xl, o.sx, o.zx, o.xf, o.pmax, s, m_off, sx_ld);
 }
 
 int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g, const RqOut& o,
                            hipStream_t s) {
   // Large problems: 256 x 256 workgroup tiles (8 waves); medium: 256 channels x 128 tokens
-  // (4 waves); small: 128 x 128 as 4 waves of 128 channels x 32 tokens.  A small launch is a chain of
-  // latencies (a few dozen workgroups, each alone on its CU, walk K stage by stage), so its waves carry
-  // half the arithmetic per stage: 13 instead of 20 us at M = 256, K = 1152.
+  // (4 waves); small: 128 x 128 as 4 waves of 128 channels x 32 tokens, or 128 x 64 with K split over two
+  // sets of such waves (below).  A small launch is a chain of latencies (a few dozen workgroups, each alone
+  // on its CU, walk K stage by stage), so its waves carry half the arithmetic per stage: 13 instead of 20 us
+  // at M = 256, K = 1152.
   // The large tiles run long enough to be limited by power (the shader clock drops under
   // sustained MFMA work on random data); there the 16x16x32 MFMA, which moves half the
   // accumulator bytes per multiply-add, is the faster one.  The smaller, latency-bound
@@ -635,6 +673,12 @@ int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, 
     return launch_cfg<2, 4, 64, 16>(o, x, Qt, M, K, r, g, s);
   }
   if (mid_tiles >= 100) return launch_cfg<2, 2, 64, 32>(o, x, Qt, M, K, r, g, s);
+  // A launch this small is held back by what one CU can load per cycle (each workgroup streams its 128 basis rows
+  // over all of K) and by the chain of stage latencies: with 128 x 64 tiles and the two halves of K on two sets
+  // of waves per workgroup it has twice the workgroups and half the stages (11 instead of 13 us at M = 256,
+  // K = 1152; 21 instead of 26 at K = 3072), as long as that is still a single round of workgroups.
+  const long small_tiles = (long)((Kv + 127) / 128) * ((M + 63) / 64);
+  if (K % 128 == 0 && small_tiles <= 256) return launch_cfg<1, 2, 64, 32, 32, 2>(o, x, Qt, M, K, r, g, s);
   return launch_cfg<1, 4, 64, 32, 32>(o, x, Qt, M, K, r, g, s);
 }
 
