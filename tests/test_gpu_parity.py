@@ -303,6 +303,30 @@ def test_end_to_end_ragged_tokens_and_outputs():
     _end_to_end(shp)
 
 
+def _random_shapes(n, seed):
+    """Seeded draw of layer shapes that straddle the launchers' decisions: token counts on both sides of every
+    tile size, K with and without the factors 64 and 128 (stage length, the small launch's split of K), every
+    group size, r from 0 up, N off the tile grid."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        g = int(rng.choice([32, 64, 128]))
+        K = 32 * int(rng.integers(2, 29))                      # 64 .. 896
+        r_choices = [r for r in range(0, K, 32) if (K - r) % g == 0]
+        if not r_choices:
+            continue
+        r = int(rng.choice(r_choices))
+        M = int(rng.choice([1, 31, 33, 63, 65, 127, 129, 200, 257, 300, 513, 640]))
+        N = int(rng.integers(8, 700))
+        out.append(I.LayerShape(f"rand{len(out)}_M{M}_K{K}_N{N}_r{r}_g{g}", M, K, N, r, g, 3, 9, len(out)))
+    return out
+
+
+@pytest.mark.parametrize("shp", _random_shapes(16, 20260516), ids=lambda s: s.name)
+def test_end_to_end_random_shapes(shp):
+    _end_to_end(shp)
+
+
 def _every(M, step):
     return np.arange(0, M, step)
 
