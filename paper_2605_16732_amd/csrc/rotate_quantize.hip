@@ -10,8 +10,10 @@
 // (l, l^32): the absmax is an in-lane max plus one cross-lane exchange, the codes are
 // packed in registers, and nothing is staged through LDS after the main loop.
 //
-// Channel tiling.  Waves own 128 "virtual" channels: the bf16 part [0, r) is padded to a
-// multiple of 128, the 4-bit part [r, K) follows, so groups never straddle a wave.
+// Channel tiling.  Waves own 128 "virtual" channels: the bf16 part [0, r), then the 4-bit part
+// [r, K) from virtual channel r_pad on, placed so that groups never straddle a wave: r_pad = r when
+// r is a multiple of the group size (the wave that holds the split point then stores both kinds),
+// else r rounded up to 128.
 //
 // Main loop.  Operand tiles are staged HBM -> registers -> LDS (two LDS stages) with an
 // XOR swizzle applied on the global side, so that the 16-byte MFMA operand reads of 16
@@ -59,8 +61,8 @@ struct RQ {
 
 // Epilogue of a wave whose accumulators are 4 x WT tiles of 32 channels x 32 tokens (32x32 MFMA layout: a lane
 // owns one token and 4 consecutive channels per register quad): the split at r, the per-group quantizer and the
-// packing, all in registers.  vb: the wave's first virtual channel (the 16-bit part padded to a multiple of 128,
-// then the 4-bit part); tok_base: its first token.
+// packing, all in registers.  vb: the wave's first virtual channel (the 16-bit part, then the 4-bit part from
+// r_pad on); tok_base: its first token.
 template <int QM, int WT>
 __device__ __forceinline__ void rq_epilogue32(const f32x16 (&acc)[4][WT], int vb, int tok_base, int M, int K, int r,
                                               int g, int r_pad, int Kv, uint16_t* __restrict__ xh,
@@ -89,9 +91,9 @@ __device__ __forceinline__ void rq_epilogue32(const f32x16 (&acc)[4][WT], int vb
           }
         }
     }
-    return;
+    if (vb + 128 <= r_pad) return;                          // (else the split point lies inside this wave's channels)
   }
-  const int cl0 = vb - r_pad;                               // first 4-bit channel of this wave
+  const int cl0 = vb - r_pad;                               // first 4-bit channel of this wave (negative: see above)
   const int KL = K - r;
   if constexpr (QM == 2) {
     // raw fp32 values (16-byte stores) and the wave tile's absolute maximum per token
@@ -157,7 +159,7 @@ __device__ __forceinline__ void rq_epilogue32(const f32x16 (&acc)[4][WT], int vb
 #pragma unroll
     for (int i = 0; i < 4; i++) {
       const int cl = cl0 + i * 32;                          // first 4-bit channel of this tile
-      const bool valid = cl < KL && m < M;
+      const bool valid = cl >= 0 && cl < KL && m < M;
       uint16_t sbits, zbits = 0;
       float sf, zf = 0.0f;
       if constexpr (ASYM) {
@@ -441,9 +443,9 @@ __global__ __launch_bounds__(WGC* WGT* KSP * 64, (RQ<WGC, WGT, BK, WVT, KSP>::WA
           }
         }
       }
-      return;
+      if (vb + 128 <= r_pad) return;                          // (else the split point lies inside this wave's channels)
     }
-    const int cl0 = vb - r_pad;                               // first 4-bit channel of this wave
+    const int cl0 = vb - r_pad;                               // first 4-bit channel of this wave (negative: see above)
     const int KL = K - r;
     if constexpr (QM == 2) {
 #pragma unroll
@@ -550,7 +552,7 @@ __global__ __launch_bounds__(WGC* WGT* KSP * 64, (RQ<WGC, WGT, BK, WVT, KSP>::WA
       }
       const float inv_q = group_inv(sf);
       const int clu = cl0 + 32 * hq;                          // first channel of unit hq
-      const bool valid = clu < KL && m < M;
+      const bool valid = clu >= 0 && clu < KL && m < M;
       if (valid && (hq % gu) == 0) {
         sx[(size_t)(clu / g) * sx_ld + m] = sbits;
         if constexpr (ASYM) zx[(size_t)(clu / g) * sx_ld + m] = zbits;
@@ -596,6 +598,15 @@ __global__ __launch_bounds__(WGC* WGT* KSP * 64, (RQ<WGC, WGT, BK, WVT, KSP>::WA
   }
 }
 
+// Virtual channel order of the tiling: the 16-bit part [0, r) first, then the 4-bit part from r_pad on.  r_pad is r
+// itself when the groups then still fall inside the 128-channel wave tiles (r a multiple of the group size: the
+// wave that holds the split point stores both kinds), else r rounded up to 128.  The fp32 output for the 8-bit
+// quantizer keeps the rounded form (its per-wave maxima are indexed by whole 128-channel tiles of the 4-bit part).
+static void virtual_channels(int K, int r, int g, bool fp32_out, int& r_pad, int& Kv) {
+  r_pad = (!fp32_out && r % g == 0) ? r : (r + 127) / 128 * 128;
+  Kv = (r_pad + (K - r) + 127) / 128 * 128;
+}
+
 template <int WGC, int WGT, int BK, int MI, int QM, int WVT, int KSP>
 static int launch_one(const uint16_t* x, const uint16_t* Qt, int M, int K, int r, int g, uint16_t* xh,
                       uint8_t* xl, uint16_t* sx, uint16_t* zx, float* xf, float* pmax, hipStream_t s, int m_off,
@@ -610,8 +621,8 @@ static int launch_one(const uint16_t* x, const uint16_t* Qt, int M, int K, int r
   if (xf) xf += (size_t)m_off * (K - r);
   if (pmax) pmax += m_off;
   using C = RQ<WGC, WGT, BK, WVT, KSP>;
-  const int r_pad = (r + 127) / 128 * 128;
-  const int Kv = r_pad + (K - r + 127) / 128 * 128;
+  int r_pad, Kv;
+  virtual_channels(K, r, g, QM == 2, r_pad, Kv);
   const int n_ct = (Kv + C::TC - 1) / C::TC;
   const int n_tt = (M + C::TT - 1) / C::TT;
   const long n_blocks = (long)n_ct * n_tt;
@@ -649,8 +660,8 @@ int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, 
   // sustained MFMA work on random data); there the 16x16x32 MFMA, which moves half the
   // accumulator bytes per multiply-add, is the faster one.  The smaller, latency-bound
   // launches are faster with the 32x32x16 MFMA and its shorter epilogue.
-  const int r_pad = (r + 127) / 128 * 128;
-  const int Kv = r_pad + (K - r + 127) / 128 * 128;
+  int r_pad, Kv;
+  virtual_channels(K, r, g, o.xf != nullptr, r_pad, Kv);
   const long n_tc256 = (Kv + 255) / 256;
   const long big_tiles = n_tc256 * ((M + 255) / 256);    // 256 channels x 256 tokens
   const long mid_tiles = n_tc256 * ((M + 127) / 128);    // 256 channels x 128 tokens
