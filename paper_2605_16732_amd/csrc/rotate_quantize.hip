@@ -683,13 +683,19 @@ int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, 
     }
     return launch_cfg<2, 4, 64, 16>(o, x, Qt, M, K, r, g, s);
   }
-  if (mid_tiles >= 100) return launch_cfg<2, 2, 64, 32>(o, x, Qt, M, K, r, g, s);
   // A launch this small is held back by what one CU can load per cycle (each workgroup streams its 128 basis rows
   // over all of K) and by the chain of stage latencies: with 128 x 64 tiles and the two halves of K on two sets
   // of waves per workgroup it has twice the workgroups and half the stages (11 instead of 13 us at M = 256,
   // K = 1152; 21 instead of 26 at K = 3072), as long as that is still a single round of workgroups.
-  const long small_tiles = (long)((Kv + 127) / 128) * ((M + 63) / 64);
+  const long n_tc128 = (Kv + 127) / 128;
+  const long small_tiles = n_tc128 * ((M + 63) / 64);      // 128 channels x 64 tokens
   if (K % 128 == 0 && small_tiles <= 256) return launch_cfg<1, 2, 64, 32, 32, 2>(o, x, Qt, M, K, r, g, s);
+  // 128 x 128 tiles (two such workgroups fit a CU) while they are resident all at once, or nearly: 14.6 instead
+  // of 22.7 us at M = 3072, K = 1152 (216 workgroups against 120 of 256 x 128); K = 3072 prefers the larger tile
+  // from one full round on (M = 1536: 44 against 49 us)
+  const long tiles128 = n_tc128 * ((M + 127) / 128);
+  if (tiles128 <= 256 || (K <= 2048 && tiles128 <= 320)) return launch_cfg<1, 4, 64, 32, 32>(o, x, Qt, M, K, r, g, s);
+  if (mid_tiles >= 100) return launch_cfg<2, 2, 64, 32>(o, x, Qt, M, K, r, g, s);
   return launch_cfg<1, 4, 64, 32, 32>(o, x, Qt, M, K, r, g, s);
 }
 
