@@ -439,7 +439,8 @@ static int launch_one(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx,
 // per CU, 256 x 128 tiles) is the fastest per tile; the kernel in this file (128 x 128 tiles, two workgroups per
 // CU) spreads a medium problem over more CUs; with few tokens both leave most of the chip idle and the split-K
 // kernel (64 x 64 outputs per workgroup, the K axis over its 8 waves) is the one with the shortest latency.
-// Measured crossovers: about 128 of the 256 x 128 tiles; about 288 of the 64 x 64 ones (512 from K = 2048 on).
+// Measured crossovers: about 128 of the 256 x 128 tiles; about 288 of the 64 x 64 ones (512 from K = 2048 on,
+// 768 from K = 8192 on: the longer K is, the longer each workgroup of the tiled kernel walks alone).
 // DIROTQ_W4A4_KERNEL=ws / tile / skinny in the environment forces one of them wherever it applies (the tests use
 // it to run all of them on the same inputs).
 enum class W4A4Schedule { kTile, kWs, kSkinny };
@@ -453,7 +454,8 @@ static W4A4Schedule w4a4_schedule(int M, int N, int K, int r) {
   const long big = (long)((M + 127) / 128) * ((N + 255) / 256);
   if (big >= 128) return W4A4Schedule::kWs;
   const long small = (long)((M + 63) / 64) * ((N + 63) / 64);
-  return (small <= 288 || (small <= 512 && K >= 2048)) ? W4A4Schedule::kSkinny : W4A4Schedule::kTile;
+  return (small <= 288 || (small <= 512 && K >= 2048) || (small <= 768 && K >= 8192)) ? W4A4Schedule::kSkinny
+                                                                                        : W4A4Schedule::kTile;
 }
 
 int launch_w4a4_gemm(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const uint16_t* zx,
