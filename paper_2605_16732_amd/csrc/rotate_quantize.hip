@@ -669,20 +669,6 @@ int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, 
     if (mid_tiles >= 100) return launch_cfg<2, 2, 32, 32>(o, x, Qt, M, K, r, g, s);
     return launch_cfg<1, 4, 32, 32, 32>(o, x, Qt, M, K, r, g, s);
   }
-  if (big_tiles >= 200) {
-    // 256 CUs take one big tile each per round.  When the last round would be less than 40-60%
-    // full, the tokens of that round are done with half-size tiles in a second launch instead,
-    // so that they spread over the whole chip.
-    const long full = big_tiles / 256 * 256, tail = big_tiles - full;
-    const int tt_big = (int)(full / n_tc256);               // token tiles covered by full rounds
-    const long tail_max = K >= 2048 ? 150 : 104;            // short tiles pay more for the second launch
-    if (full > 0 && tail > 0 && tail <= tail_max && tt_big * 256 < M && (M - tt_big * 256) % 128 == 0) {
-      int st = launch_cfg<2, 4, 64, 16>(o, x, Qt, tt_big * 256, K, r, g, s, 0, M);
-      if (st) return st;
-      return launch_cfg<2, 2, 64, 32>(o, x, Qt, M - tt_big * 256, K, r, g, s, tt_big * 256, M);
-    }
-    return launch_cfg<2, 4, 64, 16>(o, x, Qt, M, K, r, g, s);
-  }
   // A launch this small is held back by what one CU can load per cycle (each workgroup streams its 128 basis rows
   // over all of K) and by the chain of stage latencies: with 128 x 64 tiles and the two halves of K on two sets
   // of waves per workgroup it has twice the workgroups and half the stages (11 instead of 13 us at M = 256,
@@ -695,8 +681,33 @@ int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, 
   // from one full round on (M = 1536: 44 against 49 us)
   const long tiles128 = n_tc128 * ((M + 127) / 128);
   if (tiles128 <= 256 || (K <= 2048 && tiles128 <= 320)) return launch_cfg<1, 4, 64, 32, 32>(o, x, Qt, M, K, r, g, s);
-  if (mid_tiles >= 100) return launch_cfg<2, 2, 64, 32>(o, x, Qt, M, K, r, g, s);
-  return launch_cfg<1, 4, 64, 32, 32>(o, x, Qt, M, K, r, g, s);
+  // Beyond that: rounds of 256 workgroups.  A round of 256 x 128 tiles takes about 0.62 of a round of 256 x 256
+  // ones (K = 3072: 53 against 81 us, K = 12288: 186 against 300-320), so the plans compared are: all big, all
+  // half-size, or k full rounds of big tiles and the remaining tokens in a second launch of half-size ones.
+  const int cus = 256;
+  auto rounds = [&](long tiles) { return (double)((tiles + cus - 1) / cus); };
+  constexpr double MID = 0.62, SECOND_LAUNCH = 0.03;
+  double best = rounds(big_tiles);                          // plan: one launch of big tiles
+  int plan_tt = -1;                                         // -1: all big, 0: all half-size, > 0: token tiles in the big launch
+  if (rounds(mid_tiles) * MID < best) {
+    best = rounds(mid_tiles) * MID;
+    plan_tt = 0;
+  }
+  for (long k = 1; k * cus < big_tiles; k++) {
+    const long tt = k * cus / n_tc256;                      // token tiles of 256 that k rounds hold
+    if (tt <= 0 || tt * 256 >= M) continue;
+    const long rest = n_tc256 * ((M - tt * 256 + 127) / 128);
+    const double c = rounds(tt * n_tc256) + rounds(rest) * MID + SECOND_LAUNCH;
+    if (c < best) {
+      best = c;
+      plan_tt = (int)tt;
+    }
+  }
+  if (plan_tt < 0) return launch_cfg<2, 4, 64, 16>(o, x, Qt, M, K, r, g, s);
+  if (plan_tt == 0) return launch_cfg<2, 2, 64, 32>(o, x, Qt, M, K, r, g, s);
+  const int st = launch_cfg<2, 4, 64, 16>(o, x, Qt, plan_tt * 256, K, r, g, s, 0, M);
+  if (st) return st;
+  return launch_cfg<2, 2, 64, 32>(o, x, Qt, M - plan_tt * 256, K, r, g, s, plan_tt * 256, M);
 }
 
 }  // namespace dirotq
