@@ -684,7 +684,14 @@ int launch_rotate_quantize(const uint16_t* x, const uint16_t* Qt, int M, int K, 
   // Beyond that: rounds of 256 workgroups.  A round of 256 x 128 tiles takes about 0.62 of a round of 256 x 256
   // ones (K = 3072: 53 against 81 us, K = 12288: 186 against 300-320), so the plans compared are: all big, all
   // half-size, or k full rounds of big tiles and the remaining tokens in a second launch of half-size ones.
-  const int cus = 256;
+  int cus = 0;
+  {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return hip_failed(e);
+    if (cus < 1) cus = 1;
+  }
   auto rounds = [&](long tiles) { return (double)((tiles + cus - 1) / cus); };
   constexpr double MID = 0.62, SECOND_LAUNCH = 0.03;
   double best = rounds(big_tiles);                          // plan: one launch of big tiles
