@@ -54,7 +54,7 @@
  *  - Activation scales are group-major: s_x[j * M + m] for group j, token m.
  *  - The GEMM calls pick one of several schedules of the same arithmetic from the problem
  *    size (few tokens: K split over the waves of a workgroup; medium: 128 x 128 tiles;
- *    large: persistent wave-specialised workgroups).  The fp32 additions of an output are
+ *    large: persistent wave-specialised workgroups; asymmetric layers use the last two).  The fp32 additions of an output are
  *    ordered differently in each, so a token's result is deterministic for a given
  *    (M, N, K, r, g) but not bit-identical across different M.  For testing, the
  *    environment variables DIROTQ_W4A4_KERNEL (ws | tile | skinny) and

@@ -104,8 +104,9 @@ int launch_w4a16_gemm(const uint16_t* x, const void* blob, const uint16_t* bias,
 int launch_w4a4_gemm(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const uint16_t* zx,
                      const void* blob, const uint16_t* bias, int M, int N, int K, int r, int g, void* y,
                      int y_dtype, hipStream_t s);
-// symmetric activation codes only; 4-bit part not empty (wave-specialised schedule of the same arithmetic)
-int launch_w4a4_gemm_ws(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const void* blob,
+// 4-bit part not empty (wave-specialised schedule of the same arithmetic); zx: zero-points of asymmetric
+// activation codes, or NULL for symmetric ones
+int launch_w4a4_gemm_ws(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const uint16_t* zx, const void* blob,
                         const uint16_t* bias, int M, int N, int K, int r, int g, void* y, int y_dtype, hipStream_t s);
 // symmetric activation codes, few tokens: the K axis split over the waves of a workgroup (64 x 64 outputs each)
 int launch_w4a4_gemm_skinny(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const void* blob,

@@ -468,10 +468,13 @@ int launch_w4a4_gemm(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, 
                      : launch_one<GS, false, true>(xh, xl, sx, zx, blob, bias, M, N, K, r, y, s);     \
     return y_dtype ? launch_one<GS, true, false>(xh, xl, sx, zx, blob, bias, M, N, K, r, y, s)        \
                    : launch_one<GS, false, false>(xh, xl, sx, zx, blob, bias, M, N, K, r, y, s);
-  if (!zx) {
+  {
+    // (asymmetric layers: the wave-specialised schedule or this file's kernel; the few-token one has no
+    // zero-point term)
     const W4A4Schedule sch = w4a4_schedule(M, N, K, r);
-    if (sch == W4A4Schedule::kWs) return launch_w4a4_gemm_ws(xh, xl, sx, blob, bias, M, N, K, r, g, y, y_dtype, s);
-    if (sch == W4A4Schedule::kSkinny)
+    if (sch == W4A4Schedule::kWs)
+      return launch_w4a4_gemm_ws(xh, xl, sx, zx, blob, bias, M, N, K, r, g, y, y_dtype, s);
+    if (sch == W4A4Schedule::kSkinny && !zx)
       return launch_w4a4_gemm_skinny(xh, xl, sx, blob, bias, M, N, K, r, g, y, y_dtype, s);
   }
   switch (g) {

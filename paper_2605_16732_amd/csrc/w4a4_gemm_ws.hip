@@ -1,4 +1,4 @@
-// Kernel B, wave-specialised form (symmetric activation codes):
+// Kernel B, wave-specialised form (symmetric activation codes; the asymmetric ones: see the kernel's comment):
 //   y = x_h W'_h^T + sum_j s_x[:,j] s_w[:,j]^T * (q_x,j q_w,j^T)
 // (forward-computation equation of Section 4.2 of the paper).  Arithmetic as in w4a4_gemm.hip: codes run on the
 // fp8 matrix pipe as exact subnormals, the scale product of a group comes from a small fp16 MFMA, one fma per
@@ -60,6 +60,12 @@ __device__ __forceinline__ void unpack8(uint32_t p, uint32_t& even, uint32_t& od
   odd = ((p >> 4) & 0x07070707u) | (p & 0x80808080u);
 }
 
+// 8 unsigned nibbles (asymmetric activations) -> fp8 bytes u * 2^-9, exact for u = 0..15
+__device__ __forceinline__ void unpack8u(uint32_t p, uint32_t& even, uint32_t& odd) {
+  even = p & 0x0F0F0F0Fu;
+  odd = (p >> 4) & 0x0F0F0F0Fu;
+}
+
 typedef __attribute__((ext_vector_type(8))) int i32x8;
 
 // bf16 store of a wave's 64 x 64 block whose output channels all exist (N a multiple of 8): in the accumulator
@@ -115,12 +121,18 @@ __device__ __forceinline__ void tile_origin(int logical, int n_mt, int n_nt, int
 // per_xcd consecutive logical tiles, the tiles (b >> 3) + it * wpx, it = 0, 1, ...  The stage stream is continuous
 // across a workgroup's tiles: the staging waves are loading the next tile while the multiplying waves finish and
 // store the current one.
-template <int GS, bool OUT_F32>
+//
+// Asymmetric activations (ASYM): the codes of the token rows are unsigned nibbles, and the zero-point term
+// sum_j z[m,j] (s_w[n,j] sum_k q_w[n,k]) follows each tile's 4-bit stages as nzp more 16-bit stages whose rows the
+// staging waves form on the fly: per group five k-slots, weight rows b1 b2 b3 b1 b2, token rows z1 z1 z1 z2 z2,
+// with z = z1 + z2 and s_w sum q_w = b1 + b2 + b3 exact bf16 splits (only z2 b3, below 2^-24 of the term, is
+// dropped); six groups per stage (both 16-byte chunks of a lane's operand, two MFMAs per tile).
+template <int GS, bool OUT_F32, bool ASYM>
 __global__ __launch_bounds__(NT, 1) void w4a4_gemm_ws_kernel(
     const uint16_t* __restrict__ xh, const uint8_t* __restrict__ xl, const uint16_t* __restrict__ sx,
-    const uint16_t* __restrict__ wh, const uint8_t* __restrict__ wq, const uint16_t* __restrict__ sw,
-    const uint16_t* __restrict__ bias, int M, int N, int K, int r, void* __restrict__ y, int n_mt, int n_nt,
-    int per_xcd, int wpx) {
+    const uint16_t* __restrict__ zx, const uint16_t* __restrict__ wh, const uint8_t* __restrict__ wq,
+    const uint16_t* __restrict__ sw, const int16_t* __restrict__ wsum, const uint16_t* __restrict__ bias, int M, int N,
+    int K, int r, void* __restrict__ y, int n_mt, int n_nt, int per_xcd, int wpx) {
   extern __shared__ __align__(16) unsigned char smem[];
 
   const int run0 = (blockIdx.x & 7) * per_xcd, first = blockIdx.x >> 3;
@@ -138,6 +150,9 @@ __global__ __launch_bounds__(NT, 1) void w4a4_gemm_ws_kernel(
   const int nbf_real = r / 16, nbf = (nbf_real + 3) / 4 * 4;
   const int nq_real = (KL + 63) / 64, nq = (nq_real + 3) / 4 * 4;
   const int nst = nbf + nq;
+  // zero-point stages of a tile (ASYM): 6 groups each, padded to a multiple of 4 (the ring's period, and the
+  // period of the staging waves' register sets: the stage stream of the next tile meets them in the same phase)
+  const int nzp = ASYM ? ((G + 5) / 6 + 3) / 4 * 4 : 0;
 
   // ================= staging waves: HBM -> registers -> LDS ring =================
   if (w_s >= NMULT) {
@@ -194,7 +209,7 @@ __global__ __launch_bounds__(NT, 1) void w4a4_gemm_ws_kernel(
 
     // register sets: one stage each.  Loads are straight-line code of one shape, whatever the stage's kind, so
     // that the count of loads in flight is exact and a store waits for its own set only.
-    constexpr int NSETS = nsets(GS);
+    constexpr int NSETS = ASYM ? 4 : nsets(GS);          // (ASYM keeps registers free for the zero-point stages)
     uint4 rg[NSETS][3];
     uint16_t rsw[NSETS][GPS], rsx[NSETS][GPS];
     auto gload = [&](int set) {                          // loads the cursor's stage, then moves the cursor on
@@ -224,6 +239,7 @@ __global__ __launch_bounds__(NT, 1) void w4a4_gemm_ws_kernel(
       }
     };
     int sst = 0;                                         // store cursor: stage within its tile
+    int stiles = 0;                                      // tiles whose regular stages have all been stored
     auto sstore = [&](int slot, int set) {
       const int st = sst;
       unsigned char* sb = smem + slot * STAGE_BYTES;
@@ -235,10 +251,17 @@ __global__ __launch_bounds__(NT, 1) void w4a4_gemm_ws_kernel(
 #pragma unroll
         for (int u = 0; u < 3; u++) {
           uint4 e, o;
-          unpack8(rg[set][u].x, e.x, o.x);
-          unpack8(rg[set][u].y, e.y, o.y);
-          unpack8(rg[set][u].z, e.z, o.z);
-          unpack8(rg[set][u].w, e.w, o.w);
+          if (ASYM && u == 2) {                          // token rows: unsigned codes
+            unpack8u(rg[set][u].x, e.x, o.x);
+            unpack8u(rg[set][u].y, e.y, o.y);
+            unpack8u(rg[set][u].z, e.z, o.z);
+            unpack8u(rg[set][u].w, e.w, o.w);
+          } else {
+            unpack8(rg[set][u].x, e.x, o.x);
+            unpack8(rg[set][u].y, e.y, o.y);
+            unpack8(rg[set][u].z, e.z, o.z);
+            unpack8(rg[set][u].w, e.w, o.w);
+          }
           *(uint4*)(sb + soq[u]) = e;
           *(uint4*)(sb + (soq[u] ^ 16)) = o;
         }
@@ -253,7 +276,87 @@ __global__ __launch_bounds__(NT, 1) void w4a4_gemm_ws_kernel(
           if (t < TMW) *(uint2*)(smem + sos_x + slot * SSB + jj * (SROWS * 8)) = make_uint2(rsx[set][jj] & keep, 0u);
         }
       }
-      if (++sst == nst) sst = 0;
+      if (++sst == nst) {
+        sst = 0;
+        stiles++;
+      }
+    };
+    // The zero-point stages of tile `it` (ASYM): nzp intervals, each one stage into the ring and one barrier, like
+    // the regular intervals around them.  Thread t forms, for its three rows, the 16 k-slots of its half of the
+    // row: groups 6 z + 3 half + {0, 1, 2} and a zero slot.  The factors of stage z + 1 are fetched while stage z
+    // is formed (two small register sets; the regular stages' sets keep their loads meanwhile).
+    int zdone = 0;
+    size_t zcol[3];                                      // the thread's rows of the tile: output channels, token
+    uint16_t fa[2][3][3];                                // s_w bits (weight rows) or z bits (token row)
+    int16_t fb[2][2][3];                                 // code sums (weight rows)
+    auto zp_fetch = [&](int buf, int z) {
+#pragma unroll
+      for (int gg = 0; gg < 3; gg++) {
+        const size_t jc = (size_t)min(6 * z + 3 * half + gg, G - 1);
+        fa[buf][0][gg] = sw[jc * N + zcol[0]];
+        fb[buf][0][gg] = wsum[jc * N + zcol[0]];
+        fa[buf][1][gg] = sw[jc * N + zcol[1]];
+        fb[buf][1][gg] = wsum[jc * N + zcol[1]];
+        fa[buf][2][gg] = zx[jc * M + zcol[2]];
+      }
+    };
+    auto zp_phase = [&](int it) {
+      {
+        int m0, n0;
+        tile_origin(run0 + first + it * wpx, n_mt, n_nt, m0, n0);
+#pragma unroll
+        for (int u = 0; u < 3; u++) {
+          const int row = (t >> 1) + 128 * u;
+          zcol[u] = row < TNW ? (size_t)min(n0 + row, N - 1) : (size_t)min(m0 + row - TNW, M - 1);
+        }
+        zp_fetch(0, 0);
+      }
+      // v = p1 + p2 + p3 with each piece a bf16 number: truncating splits (exact, the residuals need no rounding)
+      auto hi16 = [](float v) { return __builtin_bit_cast(uint32_t, v) & 0xFFFF0000u; };
+      auto fill = [&](int slot, int buf, int z) {
+        unsigned char* sb = smem + slot * STAGE_BYTES;
+#pragma unroll
+        for (int u = 0; u < 3; u++) {
+          uint32_t k16[16];                              // the 16 k-slots as fp32 bits with the low half clear
+          k16[15] = 0u;
+#pragma unroll
+          for (int gg = 0; gg < 3; gg++) {
+            const bool live = 6 * z + 3 * half + gg < G;
+            if (u < 2) {
+              const float v = live ? f16_bits_to_f32(fa[buf][u][gg]) * (float)fb[buf][u][gg] : 0.0f;
+              const uint32_t p1 = hi16(v);
+              const float r1 = v - __builtin_bit_cast(float, p1);
+              const uint32_t p2 = hi16(r1);
+              const uint32_t p3 = hi16(r1 - __builtin_bit_cast(float, p2));
+              k16[5 * gg + 0] = p1;
+              k16[5 * gg + 1] = p2;
+              k16[5 * gg + 2] = p3;
+              k16[5 * gg + 3] = p1;
+              k16[5 * gg + 4] = p2;
+            } else {
+              const float v = live ? f16_bits_to_f32(fa[buf][2][gg]) : 0.0f;   // an fp16 value: two pieces hold it
+              const uint32_t p1 = hi16(v);
+              const uint32_t p2 = hi16(v - __builtin_bit_cast(float, p1));
+              k16[5 * gg + 0] = p1;
+              k16[5 * gg + 1] = p1;
+              k16[5 * gg + 2] = p1;
+              k16[5 * gg + 3] = p2;
+              k16[5 * gg + 4] = p2;
+            }
+          }
+          auto pair = [&](int a) { return (k16[a] >> 16) | k16[a + 1]; };    // two bf16 slots in a dword
+          *(uint4*)(sb + soq[u]) = make_uint4(pair(0), pair(2), pair(4), pair(6));
+          *(uint4*)(sb + (soq[u] ^ 16)) = make_uint4(pair(8), pair(10), pair(12), pair(14));
+        }
+      };
+      for (int z0 = 0; z0 < nzp; z0 += 4) {
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+          zp_fetch((k + 1) & 1, z0 + k + 1);             // (past the end: clamped, unused)
+          fill(k, k & 1, z0 + k);
+          __syncthreads();
+        }
+      }
     };
     // stages 0..NSETS-1 into the register sets; stages 0..2 on into ring slots 0..2, their sets reloaded
 #pragma unroll
@@ -271,6 +374,11 @@ __global__ __launch_bounds__(NT, 1) void w4a4_gemm_ws_kernel(
 #pragma unroll
       for (int k = 0; k < NSETS; k++) {
         if (k > 0 && k % NBUF == 0 && s0 + k >= n_intervals) break;
+        if constexpr (ASYM) {
+          // the store cursor stands at the first stage of a tile: the zero-point stages of the tile before it
+          // come first (also behind the last tile: the cursor wraps for the stages that nobody reads)
+          if ((k + 3) % NBUF == 0 && sst == 0 && stiles > zdone) zp_phase(zdone++);
+        }
         sstore((k + 3) % NBUF, (k + 3) % NSETS);
         gload((k + 3) % NSETS);
         __syncthreads();
@@ -389,6 +497,28 @@ __global__ __launch_bounds__(NT, 1) void w4a4_gemm_ws_kernel(
       }
     }
 
+    // ---- zero-point term (ASYM): 32 k-slots per stage, two bf16 MFMAs per tile ----
+    if constexpr (ASYM) {
+      for (int s0 = 0; s0 < nzp; s0 += 4) {
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+          const int odd = k & 1, nslot = (k + 1) % NBUF;
+#pragma unroll
+          for (int u = 0; u < 4; u++) {
+            const int i = tile_i(u), j = tile_j(odd, u);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[i][0]),
+                                                                __builtin_bit_cast(bf16x8, b[j][0]), acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[i][1]),
+                                                                __builtin_bit_cast(bf16x8, b[j][1]), acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            refill(odd, u, nslot);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          __builtin_amdgcn_s_barrier();
+        }
+      }
+    }
+
     int m0, n0;
     tile_origin(run0 + first + it * wpx, n_mt, n_nt, m0, n0);
     if (!OUT_F32 && (N & 7) == 0 && n0 + wn * 64 + 64 <= N)
@@ -398,8 +528,8 @@ __global__ __launch_bounds__(NT, 1) void w4a4_gemm_ws_kernel(
   }
 }
 
-template <int GS, bool OUT_F32>
-static int launch_one(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const void* blob,
+template <int GS, bool OUT_F32, bool ASYM>
+static int launch_one(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const uint16_t* zx, const void* blob,
                       const uint16_t* bias, int M, int N, int K, int r, void* y, hipStream_t s) {
   const BlobLayout L = blob_layout(N, K, r, GS);
   const char* bp = (const char*)blob;
@@ -418,33 +548,36 @@ static int launch_one(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx,
   // (idempotent: two threads racing here would both set the same attribute)
   static std::atomic<bool> attr_done{false};
   if (!attr_done.load(std::memory_order_acquire)) {
-    hipError_t e = hipFuncSetAttribute((const void*)w4a4_gemm_ws_kernel<GS, OUT_F32>,
+    hipError_t e = hipFuncSetAttribute((const void*)w4a4_gemm_ws_kernel<GS, OUT_F32, ASYM>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes(GS));
     if (e != hipSuccess) return hip_failed(e);
     attr_done.store(true, std::memory_order_release);
   }
-  hipLaunchKernelGGL((w4a4_gemm_ws_kernel<GS, OUT_F32>), dim3(wpx * 8), dim3(NT), smem_bytes(GS), s, xh, xl, sx,
-                     (const uint16_t*)(bp + L.off_wh), (const uint8_t*)(bp + L.off_codes),
-                     (const uint16_t*)(bp + L.off_sw), bias, M, N, K, r, y, n_mt, n_nt, per_xcd, wpx);
+  hipLaunchKernelGGL((w4a4_gemm_ws_kernel<GS, OUT_F32, ASYM>), dim3(wpx * 8), dim3(NT), smem_bytes(GS), s, xh, xl, sx,
+                     zx, (const uint16_t*)(bp + L.off_wh), (const uint8_t*)(bp + L.off_codes),
+                     (const uint16_t*)(bp + L.off_sw), (const int16_t*)(bp + L.off_wsum), bias, M, N, K, r, y, n_mt,
+                     n_nt, per_xcd, wpx);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? DIROTQ_OK : hip_failed(e);
 }
 
 }  // namespace ws
 
-int launch_w4a4_gemm_ws(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const void* blob,
+int launch_w4a4_gemm_ws(const uint16_t* xh, const uint8_t* xl, const uint16_t* sx, const uint16_t* zx, const void* blob,
                         const uint16_t* bias, int M, int N, int K, int r, int g, void* y, int y_dtype, hipStream_t s) {
+#define DIROTQ_WS_CASE(GS)                                                                                 \
+  case GS:                                                                                                 \
+    if (zx)                                                                                                \
+      return y_dtype ? ws::launch_one<GS, true, true>(xh, xl, sx, zx, blob, bias, M, N, K, r, y, s)        \
+                     : ws::launch_one<GS, false, true>(xh, xl, sx, zx, blob, bias, M, N, K, r, y, s);      \
+    return y_dtype ? ws::launch_one<GS, true, false>(xh, xl, sx, zx, blob, bias, M, N, K, r, y, s)         \
+                   : ws::launch_one<GS, false, false>(xh, xl, sx, zx, blob, bias, M, N, K, r, y, s);
   switch (g) {
-    case 32:
-      return y_dtype ? ws::launch_one<32, true>(xh, xl, sx, blob, bias, M, N, K, r, y, s)
-                     : ws::launch_one<32, false>(xh, xl, sx, blob, bias, M, N, K, r, y, s);
-    case 64:
-      return y_dtype ? ws::launch_one<64, true>(xh, xl, sx, blob, bias, M, N, K, r, y, s)
-                     : ws::launch_one<64, false>(xh, xl, sx, blob, bias, M, N, K, r, y, s);
-    case 128:
-      return y_dtype ? ws::launch_one<128, true>(xh, xl, sx, blob, bias, M, N, K, r, y, s)
-                     : ws::launch_one<128, false>(xh, xl, sx, blob, bias, M, N, K, r, y, s);
+    DIROTQ_WS_CASE(32)
+    DIROTQ_WS_CASE(64)
+    DIROTQ_WS_CASE(128)
   }
+#undef DIROTQ_WS_CASE
   return DIROTQ_ERR_SHAPE;
 }
 

@@ -105,8 +105,18 @@ def test_rotate_quantize_asym_hand_rows():
 
 
 # ------------------------------------------------------------------ kernel B
-@pytest.mark.parametrize("M,N,K,g", [(130, 200, 256, 32), (257, 136, 448, 64), (64, 129, 384, 128), (5, 8, 64, 32)])
-def test_w4a4_asym_integer_exact(M, N, K, g):
+@pytest.fixture(params=["tile", "ws"])
+def asym_schedule(request, monkeypatch):
+    """Asymmetric layers run on two schedules of kernel B (128 x 128 tiles with the zero-point passes in the tail;
+    wave-specialised workgroups whose staging waves add zero-point stages to the stage stream); the library picks by
+    problem size and the environment switch forces one, so that both run on the same inputs."""
+    monkeypatch.setenv("DIROTQ_W4A4_KERNEL", request.param)
+    return request.param
+
+
+@pytest.mark.parametrize("M,N,K,g", [(130, 200, 256, 32), (257, 136, 448, 64), (64, 129, 384, 128), (5, 8, 64, 32),
+                                     (300, 520, 832, 64)])
+def test_w4a4_asym_integer_exact(M, N, K, g, asym_schedule):
     """Unit scales, integer zero-points: y = sum_k (q_x + z) q_w is a small integer, exact in fp32."""
     _say(f"w4a4_asym integer M={M} N={N} K={K} g={g}")
     rng = np.random.default_rng(14)
@@ -128,9 +138,10 @@ def test_w4a4_asym_integer_exact(M, N, K, g):
 
 @pytest.mark.parametrize("M,N,K,r,g,use_bias", [
     (200, 136, 320, 64, 64, True), (130, 129, 288, 32, 32, False), (64, 64, 256, 128, 128, True),
-    (300, 264, 1152, 64, 64, False), (140, 72, 3072, 0, 64, False),
+    (300, 264, 1152, 64, 64, False), (140, 72, 3072, 0, 64, False), (260, 515, 224, 96, 32, True),
+    (150, 300, 416, 32, 128, True),
 ])
-def test_w4a4_asym_matches_oracle_on_identical_inputs(M, N, K, r, g, use_bias):
+def test_w4a4_asym_matches_oracle_on_identical_inputs(M, N, K, r, g, use_bias, asym_schedule):
     """Same inputs on both sides.  The zero-point term is summed from bf16 splits that drop
     less than 2^-16 of it, the rest is fp32 accumulation: 2e-5 of the largest output magnitude."""
     _say(f"w4a4_asym vs oracle M={M} N={N} K={K} r={r} g={g} bias={use_bias}")
@@ -159,6 +170,34 @@ def test_w4a4_asym_matches_oracle_on_identical_inputs(M, N, K, r, g, use_bias):
     y0 = B.w4a4_gemm_asym(*args[:3], dev(np.zeros((G, M), np.float16)), *args[4:], bias=bias_d,
                           out_dtype=torch.float32).cpu().numpy()
     assert np.abs(y0 - y32).max() > 1e-2 * scale
+
+
+def test_w4a4_asym_persistent_workgroups_take_several_tiles(monkeypatch):
+    """300 tiles of 256 x 128 on 256 CUs in the wave-specialised schedule: some workgroups run two tiles back to
+    back, so a tile's zero-point stages are followed by the next tile's regular ones.  Ragged in both directions,
+    a rank-32 branch, 8 groups (two zero-point stages of which the second is partly padding, plus two empty ones)."""
+    monkeypatch.setenv("DIROTQ_W4A4_KERNEL", "ws")
+    M, N, K, r, g = 2500, 3592, 544, 32, 64
+    _say(f"w4a4_asym persistent M={M} N={N} K={K} r={r} g={g}")
+    rng = np.random.default_rng(17)
+    G = (K - r) // g
+    xh = O.round_to_bf16(rng.standard_normal((M, r)).astype(np.float32) * 20)
+    Wh = O.round_to_bf16(rng.standard_normal((N, r)).astype(np.float32) * 0.05)
+    qx = rng.integers(0, 16, size=(M, K - r)).astype(np.uint8)
+    qw = rng.integers(-7, 8, size=(N, K - r)).astype(np.int8)
+    sx = rng.lognormal(-1, 1, size=(M, G)).astype(np.float16)
+    zx = (rng.standard_normal((M, G)) * 5).astype(np.float16)
+    sw = rng.lognormal(-5, 1, size=(N, G)).astype(np.float16)
+    bias = O.round_to_bf16(rng.standard_normal(N).astype(np.float32))
+    y32, ybf = O.combine_asym(xh, qx, sx, zx, Wh, qw, sw, g, bias)
+    blob = import_blob(Wh, qw, sw, N, K, r, g)
+    args = (dev_bf16(O.bf16_bits(xh)), dev(pack_u4(qx)), dev(np.ascontiguousarray(sx.T)),
+            dev(np.ascontiguousarray(zx.T)), blob, M, N, K, r, g)
+    bias_d = dev_bf16(O.bf16_bits(bias))
+    yf = B.w4a4_gemm_asym(*args, bias=bias_d, out_dtype=torch.float32).cpu().numpy()
+    torch.cuda.synchronize()
+    scale = np.abs(y32).max()
+    assert np.abs(yf - y32).max() <= 2e-5 * scale
 
 
 def test_prepared_blob_carries_the_code_sums():
