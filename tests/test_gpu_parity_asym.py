@@ -307,14 +307,11 @@ def test_end_to_end_asym_small_and_ragged():
     _end_to_end_asym(I.LayerShape("ragged128_a", 141, 640, 264, 128, 128, 4, 7, 1))
 
 
-def test_end_to_end_asym_flux_fc1_full_launch_every_token():
-    # every token quantized and compared; the output on every 8th token
-    shp = I.FLUX[2]
-    _end_to_end_asym(shp, y_rows=np.arange(0, shp.M, 8))
-
-
-def test_end_to_end_asym_flux_fc2_full_launch_every_token():
-    shp = I.FLUX[3]
+@pytest.mark.parametrize("idx", range(4))
+def test_end_to_end_asym_flux_layers_full_launch_every_token(idx):
+    # the four FLUX-shaped layers in the launch configuration bench.py --asym times (kernel B: the wave-specialised
+    # schedule with its zero-point stages); every token quantized and compared, the output on every 8th token
+    shp = I.FLUX[idx]
     _end_to_end_asym(shp, y_rows=np.arange(0, shp.M, 8))
 
 
